@@ -1,0 +1,105 @@
+/*
+ * ejoin -- brute-force Euclidean-distance epsilon self-join on AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Fast and Scalable Mixed Precision Euclidean Distance Calculations
+ * Using GPU Tensor Cores" (arXiv 2508.21230): every pair of points of a data set is compared,
+ * and the pairs whose Euclidean distance is <= epsilon are returned (Section 2.1, Eq. 1;
+ * Section 2.2.1 "Scenario 1").  The distance is evaluated in the expanded form
+ *     dist^2(p_i, p_j) = s_i + s_j - 2 a_ij ,   s_i = sum_k p_ik^2 ,   a_ij = sum_k p_ik p_jk
+ * (Section 3.1, Steps 1-3) with FP16 inputs and FP32 accumulation on the matrix cores.
+ *
+ * Conventions shared by all calls
+ *   - Every pointer below except `ejoin_ctx**`, `ejoin_ctx*`, `float* ms` and the strings is a
+ *     DEVICE pointer owned by the caller.  The library never frees or reallocates them.
+ *   - X holds FP16 bit patterns, row-major: point i occupies X[i*ld .. i*ld + d - 1].
+ *     `ld` (elements) must be a multiple of 64 and >= d rounded up to a multiple of 64; the
+ *     columns d .. roundup(d,64)-1 must hold zeros (the paper pads d to a multiple of 64 with
+ *     zeros, Section 4.2).  X must be 128-byte aligned (Section 3.3.6: each point 128 B aligned).
+ *     Values must be finite.
+ *   - 1 <= n < 2^32 - 256, 1 <= d <= 65536.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work and return;
+ *     results are valid once the caller has synchronised the stream.  A call must not overlap
+ *     another call on the same context.
+ *   - Return value: EJOIN_OK or a negative error code; nothing is enqueued on error.
+ *   - The squared distance the library works with is, in FP32,
+ *         d2 = max(0, fma(-2, a_ij, s_i + s_j)),       pass  <=>  d2 <= fl(eps * eps),
+ *     where a_ij and s_i are accumulated over k in ascending order on the matrix cores in
+ *     steps of 16 coordinates, so that d2(i, i) == 0 and duplicates of a point are at distance 0
+ *     exactly.  "<= epsilon" is the paper's comparison (Section 2.2.1).
+ */
+#ifndef EJOIN_H
+#define EJOIN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EJOIN_OK 0
+#define EJOIN_EINVAL (-1)       /* null pointer, size out of range, misaligned X or ld */
+#define EJOIN_EUNSUPPORTED (-2) /* device is not gfx950 / shape outside the supported range */
+#define EJOIN_EHIP (-3)         /* a HIP runtime call failed; see ejoin_last_hip_error */
+#define EJOIN_ENOMEM (-4)       /* the context's workspace could not be allocated */
+
+typedef struct ejoin_ctx ejoin_ctx;
+
+/* Create a context on HIP device `device`.  The context owns a few hundred bytes of device
+ * counters and a workspace of 4 bytes per point for the norms s_i (grown on demand by the join
+ * calls, or ahead of time by ejoin_reserve).  Host pointer out. */
+int ejoin_create(ejoin_ctx** out, int device);
+
+/* Free the context and its device memory.  The caller must have synchronised its streams. */
+int ejoin_destroy(ejoin_ctx* ctx);
+
+/* Grow the workspace so that joins of up to n points allocate nothing. */
+int ejoin_reserve(ejoin_ctx* ctx, int64_t n);
+
+/* Static, human-readable text for a return code. */
+const char* ejoin_strerror(int code);
+
+/* Text of the last HIP error seen by this context ("" if none). */
+const char* ejoin_last_hip_error(const ejoin_ctx* ctx);
+
+/* Step 1 of Section 3.1: s[i] = sum_k x_ik^2 for i < n, FP32, written to the device array s (n floats).
+ * Accumulated on the matrix cores in the same order as the Gram products of the join. */
+int ejoin_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, void* stream);
+
+/* Per-point neighbour counts (the quantity behind the paper's selectivity, Section 4.1.3).
+ *   counts[i]     (device, n x u32, overwritten)  = #{ j != i : dist(x_i, x_j) <= eps }
+ *   *total_pairs  (device, u64, overwritten)      = #{ (i, j), i < j : dist <= eps }
+ * The paper's |R| is 2 * total_pairs + n and its selectivity S is 2 * total_pairs / n. */
+int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
+                         uint32_t* counts, uint64_t* total_pairs, void* stream);
+
+/* The result set of the self-join (Section 2.2.1): every (i, j), i < j, with dist <= eps, once,
+ * plus the self pair (i, i) of every point; in no particular order, without duplicates.
+ *   pairs    (device, capacity x 2 x u32): pair p is (pairs[2p], pairs[2p+1]) with i <= j
+ *   dist2    (device, capacity x f32, or NULL): d2 of pair p (0 for self pairs)
+ *   *n_pairs (device, u64, overwritten): number of pairs FOUND.  If it exceeds `capacity`, exactly
+ *            `capacity` pairs were written and the rest dropped: run again with a larger buffer
+ *            (or size it with ejoin_selfjoin_count: needed = total_pairs + n). */
+int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
+                         uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
+
+/* Dense block of squared distances, for checking Steps 2-3 of Section 3.1 element by element:
+ *   out[r * cols + c] = d2(i0 + r, j0 + c),  0 <= r < rows, 0 <= c < cols   (device, rows*cols f32)
+ * computed with exactly the arithmetic of the join (so it is bit-identical to the dist2 the join
+ * reports for the same pair).  Requires i0 + rows <= n, j0 + cols <= n. */
+int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, int64_t i0, int64_t j0,
+                     int32_t rows, int32_t cols, float* out, void* stream);
+
+/* Kernel timing for benchmarks.  With profiling on, each join call records HIP events around its
+ * norm kernel and around its Gram/epilogue kernel on the call's stream.  ejoin_last_kernel_ms
+ * waits for those events and returns the two durations in milliseconds (host pointers). */
+int ejoin_set_profiling(ejoin_ctx* ctx, int on);
+int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* norms_ms, float* join_ms);
+
+/* Number of 256 x 256 output tiles the Gram kernel evaluates for n points (upper triangle,
+ * diagonal included): the executed matrix-core work is 2 * 256 * 256 * roundup(d,64) FLOP per tile. */
+int64_t ejoin_tiles_evaluated(int64_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EJOIN_H */

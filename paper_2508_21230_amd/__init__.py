@@ -1,0 +1,6 @@
+"""MI355X-native brute-force Euclidean-distance epsilon self-join (hot path of arXiv 2508.21230).
+
+The work is done by hand-written HIP kernels behind the C ABI declared in include/ejoin.h;
+`binding.EJoin` marshals torch device tensors to it.
+"""
+from .binding import EJoin, EJoinError, load_library, tiles_evaluated  # noqa: F401

@@ -1,0 +1,159 @@
+"""Thin Python binding of the C ABI in include/ejoin.h.
+
+Argument marshalling only: every step of the join runs in the HIP kernels of libejoin.so.
+PyTorch supplies device memory and streams.  There is no CPU fallback: if the library is not
+built or no gfx950 device is present, the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+EJOIN_OK = 0
+_lib = None
+
+
+class EJoinError(RuntimeError):
+    pass
+
+
+def load_library() -> C.CDLL:
+    """dlopen libejoin.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library()
+    lib = C.CDLL(_build.LIB)
+    vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float
+    lib.ejoin_create.restype = C.c_int
+    lib.ejoin_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.ejoin_destroy.restype = C.c_int
+    lib.ejoin_destroy.argtypes = [vp]
+    lib.ejoin_reserve.restype = C.c_int
+    lib.ejoin_reserve.argtypes = [vp, i64]
+    lib.ejoin_strerror.restype = C.c_char_p
+    lib.ejoin_strerror.argtypes = [C.c_int]
+    lib.ejoin_last_hip_error.restype = C.c_char_p
+    lib.ejoin_last_hip_error.argtypes = [vp]
+    lib.ejoin_norms.restype = C.c_int
+    lib.ejoin_norms.argtypes = [vp, vp, i64, i32, i64, vp, vp]
+    lib.ejoin_selfjoin_count.restype = C.c_int
+    lib.ejoin_selfjoin_count.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
+    lib.ejoin_selfjoin_pairs.restype = C.c_int
+    lib.ejoin_selfjoin_pairs.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_dist2_tile.restype = C.c_int
+    lib.ejoin_dist2_tile.argtypes = [vp, vp, i64, i32, i64, i64, i64, i32, i32, vp, vp]
+    lib.ejoin_set_profiling.restype = C.c_int
+    lib.ejoin_set_profiling.argtypes = [vp, C.c_int]
+    lib.ejoin_last_kernel_ms.restype = C.c_int
+    lib.ejoin_last_kernel_ms.argtypes = [vp, C.POINTER(f32), C.POINTER(f32)]
+    lib.ejoin_tiles_evaluated.restype = i64
+    lib.ejoin_tiles_evaluated.argtypes = [i64]
+    _lib = lib
+    return lib
+
+
+def tiles_evaluated(n: int) -> int:
+    return int(load_library().ejoin_tiles_evaluated(int(n)))
+
+
+class EJoin:
+    """One context (ejoin_ctx) on one GPU.  Methods mirror the C entry points."""
+
+    def __init__(self, device: int = 0):
+        if not torch.cuda.is_available():
+            raise EJoinError("no GPU visible: the epsilon self-join has no CPU path")
+        self._lib = load_library()
+        self.device = torch.device("cuda", device)
+        h = C.c_void_p()
+        self._check(self._lib.ejoin_create(C.byref(h), device), None)
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize(self.device)
+            self._lib.ejoin_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, rc: int, h):
+        if rc != EJOIN_OK:
+            msg = self._lib.ejoin_strerror(rc).decode()
+            if h:
+                extra = self._lib.ejoin_last_hip_error(h).decode()
+                if extra:
+                    msg += " [" + extra + "]"
+            raise EJoinError(f"ejoin error {rc}: {msg}")
+
+    @staticmethod
+    def _stream():
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def _x(self, X: torch.Tensor, d):
+        if X.dtype not in (torch.float16, torch.int16, torch.uint16):
+            raise EJoinError("X must hold fp16 values (torch.float16, or int16/uint16 bit patterns)")
+        if X.dim() != 2 or not X.is_cuda or X.stride(1) != 1:
+            raise EJoinError("X must be a 2-D device tensor with contiguous rows")
+        n, width = X.shape
+        ld = X.stride(0) if n > 1 else max(X.stride(0), width)
+        d = width if d is None else int(d)
+        return n, d, ld
+
+    def reserve(self, n: int):
+        self._check(self._lib.ejoin_reserve(self._h, int(n)), self._h)
+
+    def norms(self, X: torch.Tensor, d: int | None = None) -> torch.Tensor:
+        n, d, ld = self._x(X, d)
+        s = torch.empty(n, dtype=torch.float32, device=X.device)
+        self._check(self._lib.ejoin_norms(self._h, X.data_ptr(), n, d, ld, s.data_ptr(), self._stream()), self._h)
+        return s
+
+    def selfjoin_count(self, X: torch.Tensor, eps: float, d: int | None = None, counts: torch.Tensor | None = None,
+                       total: torch.Tensor | None = None):
+        """Returns (counts int32[n] holding u32 values, total int64[1]) -- device tensors, stream-ordered."""
+        n, d, ld = self._x(X, d)
+        if counts is None:
+            counts = torch.empty(n, dtype=torch.int32, device=X.device)
+        if total is None:
+            total = torch.empty(1, dtype=torch.int64, device=X.device)
+        self._check(self._lib.ejoin_selfjoin_count(self._h, X.data_ptr(), n, d, ld, float(eps), counts.data_ptr(),
+                                                   total.data_ptr(), self._stream()), self._h)
+        return counts, total
+
+    def selfjoin_pairs(self, X: torch.Tensor, eps: float, capacity: int, d: int | None = None, with_dist2: bool = True,
+                       pairs: torch.Tensor | None = None, dist2: torch.Tensor | None = None,
+                       n_pairs: torch.Tensor | None = None):
+        """Returns (pairs int32[capacity, 2] holding u32 values, dist2 float32[capacity] or None, n_pairs int64[1])."""
+        n, d, ld = self._x(X, d)
+        capacity = int(capacity)
+        if pairs is None:
+            pairs = torch.empty((max(capacity, 1), 2), dtype=torch.int32, device=X.device)
+        if dist2 is None and with_dist2:
+            dist2 = torch.empty(max(capacity, 1), dtype=torch.float32, device=X.device)
+        if n_pairs is None:
+            n_pairs = torch.empty(1, dtype=torch.int64, device=X.device)
+        self._check(self._lib.ejoin_selfjoin_pairs(self._h, X.data_ptr(), n, d, ld, float(eps), pairs.data_ptr(),
+                                                   dist2.data_ptr() if dist2 is not None else None, capacity,
+                                                   n_pairs.data_ptr(), self._stream()), self._h)
+        return pairs, dist2, n_pairs
+
+    def dist2_tile(self, X: torch.Tensor, i0: int, j0: int, rows: int, cols: int, d: int | None = None) -> torch.Tensor:
+        n, d, ld = self._x(X, d)
+        out = torch.empty((rows, cols), dtype=torch.float32, device=X.device)
+        self._check(self._lib.ejoin_dist2_tile(self._h, X.data_ptr(), n, d, ld, int(i0), int(j0), int(rows), int(cols),
+                                               out.data_ptr(), self._stream()), self._h)
+        return out
+
+    def set_profiling(self, on: bool):
+        self._check(self._lib.ejoin_set_profiling(self._h, 1 if on else 0), self._h)
+
+    def last_kernel_ms(self) -> tuple[float, float]:
+        a, b = C.c_float(), C.c_float()
+        self._check(self._lib.ejoin_last_kernel_ms(self._h, C.byref(a), C.byref(b)), self._h)
+        return float(a.value), float(b.value)

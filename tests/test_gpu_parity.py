@@ -1,0 +1,210 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import datagen
+from oracle import oracle as orc
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ej():
+    import paper_2508_21230_amd as pkg
+    e = pkg.EJoin(0)
+    yield e
+    e.close()
+
+
+def dev(X):
+    return torch.from_numpy(X.view(np.int16)).cuda()
+
+
+def pad(X, ld):
+    out = np.zeros((X.shape[0], ld), dtype=np.uint16)
+    out[:, :X.shape[1]] = X
+    return out
+
+
+def run_pairs(ej, Xd, eps, capacity, d=None, with_dist2=True):
+    p, d2, npairs = ej.selfjoin_pairs(Xd, eps, capacity, d=d, with_dist2=with_dist2)
+    torch.cuda.synchronize()
+    return parity.to_host_pairs(p, d2, npairs)
+
+
+def small_case(workload, n, S):
+    X = datagen.generate(workload, n=n)
+    P = orc.decode(X)
+    eps = orc.select_eps_all_pairs(P, S)
+    return X, P, eps
+
+
+# ------------------------------------------------------------------ Step 1: norms
+@pytest.mark.parametrize("workload,n", [(1, 1000), (3, 777), (4, 300)])
+def test_norms_against_oracle(ej, workload, n):
+    print(f"norms workload={workload} n={n}", flush=True)
+    X = datagen.generate(workload, n=n)
+    P = orc.decode(X)
+    s = ej.norms(dev(X)).cpu().numpy().astype(np.float64)
+    want = orc.norms(P)
+    d = X.shape[1]
+    # one RNE rounding per 16-wide MFMA step on a running sum <= s: |err| <= (d/16 + 1) * 2^-24 * s
+    assert np.all(np.abs(s - want) <= (d / 16 + 1) * 2.0**-24 * want)
+
+
+# ------------------------------------------------------------------ Steps 2-3: dense tile
+@pytest.mark.parametrize("workload,n,i0,j0,rows,cols", [(1, 600, 0, 0, 600, 600), (3, 500, 37, 250, 301, 199), (4, 400, 390, 5, 10, 33)])
+def test_dist2_tile_against_oracle(ej, workload, n, i0, j0, rows, cols):
+    print(f"dist2_tile workload={workload} n={n} block=({i0},{j0},{rows},{cols})", flush=True)
+    X = datagen.generate(workload, n=n)
+    P = orc.decode(X)
+    got = ej.dist2_tile(dev(X), i0, j0, rows, cols).cpu().numpy().astype(np.float64)
+    want = orc.dist2_block(P, i0, rows, j0, cols)
+    s = orc.norms(P)
+    tol = np.maximum(parity.REL * want, parity.FLOOR * (s[i0:i0 + rows, None] + s[None, j0:j0 + cols]))
+    assert np.all(np.abs(got - want) <= tol)
+    if i0 == j0 and rows == cols:
+        assert np.all(np.diag(got) == 0.0)  # norms are the Gram diagonal bit for bit
+        assert np.array_equal(got, got.T)
+
+
+# ------------------------------------------------------------------ the join, element by element
+@pytest.mark.parametrize("workload,n,S", [(1, 4096, 32), (2, 5000, 64), (3, 3000, 16), (4, 2500, 128), (5, 3333, 64)])
+def test_selfjoin_pairs_against_oracle(ej, workload, n, S):
+    print(f"selfjoin_pairs workload={workload} n={n} S={S}", flush=True)
+    X, P, eps = small_case(workload, n, S)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    pairs, d2, found = run_pairs(ej, dev(X), eps, capacity=ora_pairs.shape[0] + 4096)
+    assert found == pairs.shape[0]
+    st = parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+    print("  ", st, flush=True)
+    assert st["overlap_accuracy"] >= 0.9994  # the paper's worst overlap accuracy against FP64 (Table "accuracy")
+    assert abs(st["dist_err_mean"]) < 1e-4
+
+
+def test_join_dist2_is_bit_identical_to_dense_tile(ej):
+    X, P, eps = small_case(2, 1500, 40)
+    Xd = dev(X)
+    pairs, d2, found = run_pairs(ej, Xd, eps, capacity=200000)
+    dense = ej.dist2_tile(Xd, 0, 0, 1500, 1500).cpu().numpy()
+    assert np.array_equal(dense[pairs[:, 0], pairs[:, 1]], d2)
+    # and the filter is exactly "d2 <= fl(eps*eps)" on those values
+    e2 = np.float32(eps) * np.float32(eps)
+    iu = np.triu_indices(1500, 1)
+    assert int((dense[iu] <= e2).sum()) + 1500 == found
+
+
+def test_count_mode_equals_histogram_of_pair_mode(ej):
+    X, P, eps = small_case(5, 4000, 50)
+    Xd = dev(X)
+    pairs, _, found = run_pairs(ej, Xd, eps, capacity=400000, with_dist2=False)
+    counts, total = ej.selfjoin_count(Xd, eps)
+    torch.cuda.synchronize()
+    counts = counts.cpu().numpy().view(np.uint32)
+    ns = pairs[pairs[:, 0] != pairs[:, 1]]
+    hist = np.bincount(ns[:, 0], minlength=4000) + np.bincount(ns[:, 1], minlength=4000)
+    assert np.array_equal(counts, hist)
+    assert int(total.cpu()[0]) == ns.shape[0] == found - 4000
+    # against the oracle: counts may differ only through boundary pairs
+    oc, ot = orc.selfjoin_count(P, eps)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    st = parity.check_pair_sets(P, eps, pairs, None, ora_pairs, ora_d2)
+    assert abs(int(ot) - ns.shape[0]) <= st["only_gpu"] + st["only_oracle"]
+
+
+def test_run_to_run_same_set(ej):
+    X, P, eps = small_case(2, 3000, 64)
+    Xd = dev(X)
+    a, da, _ = run_pairs(ej, Xd, eps, capacity=300000)
+    b, db, _ = run_pairs(ej, Xd, eps, capacity=300000)
+    ka, kb = orc.pair_keys(a), orc.pair_keys(b)
+    oa, ob = np.argsort(ka), np.argsort(kb)
+    assert np.array_equal(ka[oa], kb[ob]) and np.array_equal(da[oa], db[ob])
+
+
+# ------------------------------------------------------------------ edge cases
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 255, 256, 257, 1000])
+@pytest.mark.parametrize("d", [64, 192])
+def test_edge_sizes(ej, n, d):
+    print(f"edge n={n} d={d}", flush=True)
+    rng = np.random.default_rng(n * 1000 + d)
+    X = rng.random((n, d), dtype=np.float32).astype(np.float16).view(np.uint16)
+    P = orc.decode(X)
+    eps = np.float32(math.sqrt(d / 6.0) * 0.9) if n > 1 else np.float32(1.0)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    pairs, d2, found = run_pairs(ej, dev(X), eps, capacity=n * (n + 1) // 2 + 8)
+    assert found == pairs.shape[0]
+    parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+
+
+def test_unpadded_d_with_zero_columns(ej):
+    # d = 100 stored with ld = 128 and zero padding (the paper pads d to a multiple of 64 with zeros)
+    rng = np.random.default_rng(5)
+    X = rng.random((700, 100), dtype=np.float32).astype(np.float16).view(np.uint16)
+    P = orc.decode(X)
+    eps = orc.select_eps_all_pairs(P, 20)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    pairs, d2, found = run_pairs(ej, dev(pad(X, 128)), eps, capacity=40000, d=100)
+    parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+
+
+def test_eps_zero_and_duplicates(ej):
+    X = datagen.generate(1, n=700)
+    X[300] = X[5]
+    X[699] = X[5]
+    X[256] = X[255]
+    P = orc.decode(X)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, 0.0)
+    pairs, d2, found = run_pairs(ej, dev(X), 0.0, capacity=2000)
+    # duplicates are at distance exactly 0 on the GPU too (norms are the Gram diagonal), so the sets are equal
+    k = np.argsort(orc.pair_keys(pairs))
+    assert np.array_equal(pairs[k], ora_pairs) and np.all(d2 == 0.0)
+
+
+def test_all_identical_points_and_eps_huge(ej):
+    n = 300
+    X = np.tile(datagen.generate(1, n=1), (n, 1))
+    pairs, d2, found = run_pairs(ej, dev(X), 0.0, capacity=n * (n + 1) // 2)
+    assert found == n * (n + 1) // 2 == pairs.shape[0] and np.all(d2 == 0.0)
+    assert np.unique(orc.pair_keys(pairs)).size == found
+    X = datagen.generate(1, n=n)
+    pairs, d2, found = run_pairs(ej, dev(X), 1000.0, capacity=n * (n + 1) // 2)
+    assert found == n * (n + 1) // 2 and np.unique(orc.pair_keys(pairs)).size == found
+    counts, total = ej.selfjoin_count(dev(X), 1000.0)
+    assert int(total.cpu()[0]) == n * (n - 1) // 2 and np.all(counts.cpu().numpy() == n - 1)
+
+
+def test_capacity_overflow_reports_found_and_writes_capacity(ej):
+    X, P, eps = small_case(1, 1024, 32)
+    Xd = dev(X)
+    full, _, found = run_pairs(ej, Xd, eps, capacity=100000)
+    cap = 1000
+    p = torch.full((cap + 64, 2), -1, dtype=torch.int32, device="cuda")
+    _, _, npairs = ej.selfjoin_pairs(Xd, eps, cap, pairs=p, with_dist2=False)
+    torch.cuda.synchronize()
+    assert int(npairs.cpu()[0]) == found > cap
+    h = p.cpu().numpy()
+    assert np.all(h[cap:] == -1), "wrote past capacity"
+    got = h[:cap].view(np.uint32)
+    assert np.all(np.isin(orc.pair_keys(got), orc.pair_keys(full)))
+    assert np.unique(orc.pair_keys(got)).size == cap
+
+
+def test_invalid_arguments_are_rejected(ej):
+    import paper_2508_21230_amd as pkg
+    X = torch.zeros((10, 128), dtype=torch.float16, device="cuda")
+    with pytest.raises(pkg.EJoinError):
+        ej.selfjoin_pairs(X[:, :100], 1.0, 10)          # ld = 128 but d = 100 is fine; d > ld is not
+        ej.selfjoin_pairs(X, 1.0, 10, d=200)
+    with pytest.raises(pkg.EJoinError):
+        ej.selfjoin_pairs(X, -1.0, 10)
+    Y = torch.zeros((10, 96), dtype=torch.float16, device="cuda")
+    with pytest.raises(pkg.EJoinError):
+        ej.norms(Y)                                      # ld not a multiple of 64
+    Z = torch.zeros(10 * 128 + 8, dtype=torch.float16, device="cuda")[8:].view(10, 128)
+    with pytest.raises(pkg.EJoinError):
+        ej.norms(Z)                                      # base not 128-byte aligned
