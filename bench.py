@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the epsilon self-join hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic workload that is already resident
+in HBM: norm kernel, counter reset, Gram + threshold + compaction kernel (pair list with dist2).
+Prints ONE JSON line.  `value` is the paper's derived throughput 2*n^2*d / t (Section 4.1.1:
+total operations of the all-pairs comparison divided by the measured time), which credits the
+use of symmetry as speed; `roofline.achieved` counts only the matrix-core work actually
+executed (upper-triangular 256x256 tiles) against the dense FP16 MFMA peak.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP16_TFLOPS = 2500.0  # MI355X dense FP16 MFMA, published
+
+
+def load_eps(workload: int, S: int) -> float:
+    with open(os.path.join(ROOT, "paper_2508_21230_amd", "workloads_eps.json")) as f:
+        return float(json.load(f)[str(workload)]["eps"][str(S)]["eps"])
+
+
+def cpu_baseline(X, workload, eps, budget_rows):
+    """The CPU oracle as it stands, timed on a bounded sample: `budget_rows` query rows against all n points."""
+    import datagen
+    from oracle import oracle as orc
+    n, d = X.shape
+    P = orc.decode(X)
+    rows = datagen.query_rows(workload, budget_rows, n=n)
+    t0 = time.perf_counter()
+    rs, nbr, d2 = orc.rows_join(P, eps, rows)  # sizes, then fills: two passes over the sample
+    dt = time.perf_counter() - t0
+    evals = 2 * rows.size * (n - 1)
+    return dict(value=2.0 * d * evals / dt / 1e12, unit="TFLOP/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"{rows.size} seeded query rows x all {n} points, FP64 difference form, evaluated twice (size pass + fill pass): "
+                       f"{evals} distance evaluations in {dt:.2f} s; extrapolated full n(n-1)/2 join: {n * (n - 1) / 2 / (evals / dt):.0f} s",
+                distance_evals_per_s=evals / dt)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", type=int, default=3, help="workload id 1..5 (datagen.WORKLOADS)")
+    ap.add_argument("--selectivity", type=int, default=None)
+    ap.add_argument("--mode", choices=["pairs", "count"], default="pairs")
+    ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one MI355X per box); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import datagen
+    import paper_2508_21230_amd as pkg
+
+    w = args.workload
+    spec = datagen.WORKLOADS[w]
+    S = args.selectivity or spec["selectivity"][0]
+    n = args.n or spec["n"]
+    d = spec["d"]
+    eps = load_eps(w, S)
+    X = datagen.generate(w, n=n)
+    Xd = torch.from_numpy(X.view(np.int16)).to("cuda:0")
+    ej = pkg.EJoin(0)
+    ej.reserve(n)
+    expect_pairs = int(n * (S / 2 * (n / spec["n"]) + 1))
+    capacity = int(expect_pairs * 1.5) + (1 << 20)
+    if args.mode == "pairs":
+        pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
+        dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
+        npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        step = lambda: ej.selfjoin_pairs(Xd, eps, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
+    else:
+        counts = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        step = lambda: ej.selfjoin_count(Xd, eps, counts=counts, total=npairs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ej.set_profiling(True)
+    join_ms, norm_ms = [], []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        a, b = ej.last_kernel_ms()  # waits for this step's events (HIP events on the launch stream)
+        norm_ms.append(a)
+        join_ms.append(b)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ej.set_profiling(False)
+    found = int(npairs.cpu()[0])
+    ms_per_step = dt / args.steps * 1e3
+    dk = (d + 63) // 64 * 64
+    tiles = pkg.tiles_evaluated(n)
+    flop_exec = 2.0 * 256 * 256 * dk * tiles
+    jm = sum(join_ms) / len(join_ms)
+    achieved = flop_exec / (jm * 1e-3) / 1e12
+    emitted = found + (0 if args.mode == "pairs" else 0)
+    out = {
+        "metric": "self-join distance TFLOPS (2*n^2*d / t)",
+        "value": 2.0 * n * n * d / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 inputs, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{w - 1}]: n={n}, d={d}, {spec['kind']}, S={S}, eps={eps:.7g}, mode={args.mode}",
+                   "n": n, "d": d, "selectivity_target": S, "eps": eps, "mode": args.mode},
+        "pairs_found": found,
+        "pairs_per_s": emitted / (ms_per_step * 1e-3),
+        "achieved_selectivity": (2.0 * (found - n) / n) if args.mode == "pairs" else 2.0 * found / n,
+        "kernel_ms": {"norms": sum(norm_ms) / len(norm_ms), "join": jm, "join_min": min(join_ms)},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS,
+                     "traffic": None, "kernel": "k_join", "flop_per_launch": flop_exec, "tiles": tiles},
+    }
+    if not args.no_cpu_baseline:
+        rows = args.cpu_rows or max(8, int(2.0e12 / (n * d * 16)))  # ~10-30 s of host work
+        out["cpu_baseline"] = cpu_baseline(X, w, eps, rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -22,10 +22,15 @@
  *     another call on the same context.
  *   - Return value: EJOIN_OK or a negative error code; nothing is enqueued on error.
  *   - The squared distance the library works with is, in FP32,
- *         d2 = max(0, fma(-2, a_ij, s_i + s_j)),       pass  <=>  d2 <= fl(eps * eps),
- *     where a_ij and s_i are accumulated over k in ascending order on the matrix cores in
- *     steps of 16 coordinates, so that d2(i, i) == 0 and duplicates of a point are at distance 0
- *     exactly.  "<= epsilon" is the paper's comparison (Section 2.2.1).
+ *         acc' = a_ij - s_i/2 - s_j/2,    d2 = max(0, -2 acc'),    pass  <=>  acc' >= -fl(eps * eps) / 2,
+ *     where a_ij and s_i are accumulated over k in ascending order on the matrix cores in steps
+ *     of 16 coordinates, and the two norm terms are added by one more matrix-core step (Step 3 of
+ *     Section 3.1 folded into the accumulation).  d2(i, i) == 0 and duplicates of a point are at
+ *     distance 0 exactly.  "<= epsilon" is the paper's comparison (Section 2.2.1).
+ *   - Data range: every s_i = sum_k x_ik^2 must be finite and below 2^31 (the paper's method
+ *     assumes data commensurate with the FP16 range, Section 4.5).  This is detected on the
+ *     device: a join over data outside the range reports zero pairs / zero counts and
+ *     ejoin_status returns a non-zero status.
  */
 #ifndef EJOIN_H
 #define EJOIN_H
@@ -45,8 +50,8 @@ extern "C" {
 typedef struct ejoin_ctx ejoin_ctx;
 
 /* Create a context on HIP device `device`.  The context owns a few hundred bytes of device
- * counters and a workspace of 4 bytes per point for the norms s_i (grown on demand by the join
- * calls, or ahead of time by ejoin_reserve).  Host pointer out. */
+ * status words and a workspace of 20 bytes per point (the norms s_i and their FP16 split; grown on
+ * demand by the join calls with hipMalloc, or ahead of time by ejoin_reserve).  Host pointer out. */
 int ejoin_create(ejoin_ctx** out, int device);
 
 /* Free the context and its device memory.  The caller must have synchronised its streams. */
@@ -89,9 +94,18 @@ int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
 int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, int64_t i0, int64_t j0,
                      int32_t rows, int32_t cols, float* out, void* stream);
 
+/* Blocks until the context's device is idle enough to read the status word of the last join or
+ * dense-tile call, and stores it in *status (host pointer):
+ *   0 = ok, 1 = some s_i >= 2^31 (outside the supported data range), 2 = Inf/NaN in the input. */
+#define EJOIN_STATUS_OK 0
+#define EJOIN_STATUS_NORM_RANGE 1
+#define EJOIN_STATUS_NONFINITE 2
+int ejoin_status(ejoin_ctx* ctx, int* status);
+
 /* Kernel timing for benchmarks.  With profiling on, each join call records HIP events around its
  * norm kernel and around its Gram/epilogue kernel on the call's stream.  ejoin_last_kernel_ms
- * waits for those events and returns the two durations in milliseconds (host pointers). */
+ * waits for those events and returns the two durations in milliseconds (host pointers):
+ * norms_ms covers the preparation kernels (reset, norms, FP16 split), join_ms the join kernel. */
 int ejoin_set_profiling(ejoin_ctx* ctx, int on);
 int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* norms_ms, float* join_ms);
 

@@ -26,36 +26,45 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 // ------------------------------------------------------------------------------------------
 // Tiling constants
 // ------------------------------------------------------------------------------------------
-constexpr int TILE = 256;          // a workgroup computes a TILE x TILE block of the distance matrix
-constexpr int KSLICE = 64;         // coordinates per LDS stage (128 B per row)
-constexpr int THREADS = 512;       // 8 wavefronts: 2 (rows) x 4 (columns), wave tile 128 x 64
-constexpr int SB = 16;             // tiles per super-block edge (one super-block = 256 tiles = one pass of the chip)
-constexpr int PANEL_BYTES = TILE * KSLICE * 2;      // 32 KB : one operand panel of one stage
-constexpr int STAGE_BYTES = 2 * PANEL_BYTES;        // A panel + B panel
-constexpr int NORM_OFF = 2 * STAGE_BYTES;           // two stages, then the norm staging area
-constexpr int NORM_BYTES = 2 * 2 * TILE * 4;        // [tile parity][A|B][TILE] floats
-constexpr int SLOT_OFF = NORM_OFF + NORM_BYTES;     // [tile parity] next-tile slots (int4 each)
-constexpr int LDS_BYTES = SLOT_OFF + 2 * 16;
+constexpr int TILE = 256;     // a workgroup computes a TILE x TILE block of the distance matrix
+constexpr int KPAD = 64;      // d is processed rounded up to a multiple of KPAD (zero padded by the caller)
+constexpr int KSLICE = 32;    // coordinates per LDS stage (64 B per row)
+constexpr int NSTAGE = 4;     // ring of LDS stages; up to NSTAGE-1 slices are in flight from L2/HBM
+constexpr int THREADS = 512;  // 8 wavefronts: 2 (rows) x 4 (columns), wave tile 128 x 64
+constexpr int SB = 16;        // tiles per super-block edge (one super-block = 256 tiles = one pass of the chip)
+constexpr int PANEL_BYTES = TILE * KSLICE * 2;  // 16 KB : one operand panel of one stage
+constexpr int STAGE_BYTES = 2 * PANEL_BYTES;    // A panel + B panel
+constexpr int AUX_OFF = NSTAGE * STAGE_BYTES;   // [tile parity][A rows | B rows][TILE] x 16 B augmentation rows
+constexpr int AUX_BYTES = 2 * 2 * TILE * 16;
+constexpr int ZERO_OFF = AUX_OFF + AUX_BYTES;   // 2 KB of zeros
+constexpr int ZERO_BYTES = 2048;
+constexpr int STG_OFF = ZERO_OFF + ZERO_BYTES;          // per-wave result staging: STG_CAP entries of (i, j, d2)
+constexpr int STG_CAP = 128;
+constexpr int STG_WAVE_BYTES = STG_CAP * 12;
+constexpr int LDS_BYTES = STG_OFF + 8 * STG_WAVE_BYTES;
 constexpr int NUM_XCD = 8;
+static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 
-// LDS layout of a panel: row r (0..255) occupies bytes [r*128, r*128+128); its eight 16-byte
-// chunks are stored permuted, chunk c at position c ^ ((r >> 1) & 7).  With 64 banks of 4 B a
-// ds_read_b128 serves 16 lanes per clock; 16 consecutive rows at the same logical chunk then
-// fall into 16 distinct 16-byte bank groups (measured: 241 B/clk/CU against 128 for r & 7).
-// This is the role the XOR swizzle of Section 3.3.5 (Eq. 2) plays on the A100's 32 banks.
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+// Device status word written by k_aux, read by the other kernels.
+constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
+
+// LDS layout of a panel: row r (0..255) occupies bytes [r*64, r*64+64); its four 16-byte chunks
+// are stored permuted, chunk c at position c ^ ((r >> 2) & 3).  The LDS has 64 banks of 4 B and a
+// ds_read_b128 serves 16 lanes per clock; 16 consecutive rows at the same logical chunk then fall
+// into 16 distinct 16-byte bank groups (4 rows per 256 B bank line x 4 positions).  This is the
+// role the XOR swizzle of Section 3.3.5 (Eq. 2) plays on the A100's 32 banks.
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
 struct JoinArgs {
   const uint16_t* X;
-  const float* s;
+  const uint4* H;          // per point: the 16-byte augmentation row, see k_aux
+  const uint32_t* status;  // device status word
   int64_t n;
   int64_t ld;
-  int nslices;  // roundup(d, 64) / 64
-  float eps2;
+  int nslices;  // roundup(d, 64) / 32
+  float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntiles;  // ceil(n / TILE)
   uint32_t nsb;     // ceil(ntiles / SB)
-  uint32_t items_per_xcd;
-  uint32_t* queue;  // NUM_XCD work counters
   // pair mode
   uint32_t* pairs;
   float* dist2;
@@ -69,11 +78,13 @@ struct JoinArgs {
 // ------------------------------------------------------------------------------------------
 // Small kernels
 // ------------------------------------------------------------------------------------------
-__global__ void k_reset(uint32_t* queue, unsigned long long* c0, unsigned long long* c1) {
-  if (threadIdx.x < NUM_XCD) queue[threadIdx.x] = 0;
+__global__ void k_reset(uint32_t* status_and_max, unsigned long long* c0) {
   if (threadIdx.x == 0) {
+    if (status_and_max) {
+      status_and_max[0] = ST_OK;
+      status_and_max[1] = 0;
+    }
     if (c0) *c0 = 0;
-    if (c1) *c1 = 0;
   }
 }
 
@@ -86,9 +97,10 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 // Gram block of those points is accumulated with the same MFMA steps, in the same k order, as
 // the join kernel uses, and its diagonal is stored.  That makes s_i bit-identical to a_ii, and
 // to a_ij for a duplicate j of i, so duplicates come out at distance exactly 0.  (The paper
-// matches its norm rounding to its tensor cores' for the same reason.)
+// matches its norm rounding to its tensor cores' for the same reason.)  Also tracks max_i s_i
+// (as FP32 bits; s >= 0 so unsigned order is numeric order, and NaN/Inf sort above every finite value).
 __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t ld, int k16steps,
-                                               float* __restrict__ s) {
+                                               float* __restrict__ s, uint32_t* __restrict__ max_bits) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t row0 = blk * 32;
@@ -106,6 +118,7 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   // row = 8*(r/4) + 4*hi + r%4 ; the diagonal element of column c is in the lane whose
   // hi equals bit 2 of c, register 4*(c/8) + c%4.
   const int c = lane & 31, hi = lane >> 5;
+  uint32_t bits = 0;
   if (((c >> 2) & 1) == hi && row0 + c < n) {
     const int want = 4 * (c >> 3) + (c & 3);
     float v = 0.f;
@@ -113,13 +126,73 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
     for (int r = 0; r < 16; ++r)
       if (r == want) v = acc[r];
     s[row0 + c] = v;
+    bits = __float_as_uint(v);
+  }
+  if (max_bits) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const uint32_t o = (uint32_t)__shfl_xor((int)bits, off);
+      bits = bits > o ? bits : o;
+    }
+    if (lane == 0) atomicMax(max_bits, bits);
   }
 }
 
+// Rows past the end of the data set use this augmentation row: -60000 in place of -s/2, so that
+// none of their pairs can pass the filter (and nothing non-finite enters the matrix cores).
+__device__ __forceinline__ uint4 aux_row_out_of_range() { return make_uint4(0xFB53u /* -60000 in FP16 */, 0u, 0x3C003C00u, 0x3C00u); }
+
+// Augmentation rows.  Step 3 of Section 3.1 (dist^2 = s_i + s_j - 2 a_ij) is folded into the
+// matrix-core accumulation: after the d/16 Gram steps one more 16-wide MFMA step adds
+// -s_i/2 - s_j/2 to a_ij, so the accumulator ends as acc' = -dist^2 / 2 and the filter becomes a
+// sign-like test against -eps^2/2.  -s/2 is FP32; it is split exactly into three FP16 pieces
+// p1 + p2 + p3 (scaled by 2^-m so that p1 fits FP16; m = 0 whenever max s < 65536).  Point i's
+// 16-byte row is  H_i = { p1, p2, p3, 0, c, c, c, 0 }  with c = 2^m.  As the A operand of the extra
+// step a row is used as is (k = 0..7; k = 8..15 are zero), as the B operand its two halves are
+// swapped, { c, c, c, 0, q1, q2, q3, 0 }, so that  A_i . B_j = c (p1+p2+p3)_i + c (q1+q2+q3)_j
+// = -s_i/2 - s_j/2  (every product is exact in FP32).
+// Rows n .. npad-1 (npad = n rounded up to a multiple of the tile edge) get the out-of-range row.
+__global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max, uint4* __restrict__ H) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t mb = status_and_max[1];
+  int m = 0;
+  uint32_t st = ST_OK;
+  if (mb >= 0x7f800000u) st = ST_NONFINITE;  // Inf or NaN among the norms
+  else {
+    const int e = (int)(mb >> 23) - 127;  // max s < 2^(e+1)
+    m = e > 15 ? e - 15 : 0;
+    if (m > 15) st = ST_NORM_RANGE;  // 2^m must be an FP16 value: needs max s < 2^31
+  }
+  if (i == 0) status_and_max[0] = st;
+  if (i >= npad) return;
+  if (i >= n) {
+    H[i] = aux_row_out_of_range();
+    return;
+  }
+  uint4 h = make_uint4(0, 0, 0, 0);
+  if (st == ST_OK) {
+    const float v = ldexpf(-0.5f * s[i], -m);
+    const _Float16 p1 = (_Float16)v;
+    const float r1 = v - (float)p1;
+    const _Float16 p2 = (_Float16)r1;
+    const _Float16 p3 = (_Float16)(r1 - (float)p2);
+    const _Float16 c = (_Float16)ldexpf(1.f, m);
+    auto bits = [](_Float16 x) { return (uint32_t)__builtin_bit_cast(uint16_t, x); };
+    h.x = bits(p1) | (bits(p2) << 16);
+    h.y = bits(p3);
+    h.z = bits(c) | (bits(c) << 16);
+    h.w = bits(c);
+  }
+  H[i] = h;
+}
+
+__device__ __forceinline__ half8 as_half8(uint4 v) { return __builtin_bit_cast(half8, v); }
+
 // Dense block of squared distances with the join's arithmetic: one wavefront per 32 x 32 block.
-__global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ X, const float* __restrict__ s, int64_t n,
-                                                  int64_t ld, int k16steps, int64_t i0, int64_t j0, int rows, int cols,
-                                                  float* __restrict__ out) {
+__global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ H,
+                                                  const uint32_t* __restrict__ status, int64_t n, int64_t ld, int k16steps,
+                                                  int64_t i0, int64_t j0, int rows, int cols, float* __restrict__ out) {
+  if (*status != ST_OK) return;
   const int lane = threadIdx.x & 63;
   const int bi = blockIdx.y * 32, bj = blockIdx.x * 32;
   int64_t ra = i0 + bi + (lane & 31), rb = j0 + bj + (lane & 31);
@@ -130,16 +203,19 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
   float16v acc;
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
   for (int k = 0; k < k16steps; ++k) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(pa[2 * k], pb[2 * k], acc, 0, 0, 0);
+  uint4 ha = make_uint4(0, 0, 0, 0), hb = ha;
+  if (lane < 32) {
+    ha = H[ra];
+    const uint4 t = H[rb];
+    hb = make_uint4(t.z, t.w, t.x, t.y);
+  }
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ha), as_half8(hb), acc, 0, 0, 0);
   const int c = bj + (lane & 31), hi = lane >> 5;
   if (c < cols) {
-    const float sj = s[j0 + c];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int rr = bi + 8 * (r >> 2) + 4 * hi + (r & 3);
-      if (rr < rows) {
-        const float t = s[i0 + rr] + sj;
-        out[(int64_t)rr * cols + c] = fmaxf(fmaf(-2.f, acc[r], t), 0.f);
-      }
+      if (rr < rows) out[(int64_t)rr * cols + c] = fmaxf(-2.f * acc[r], 0.f);
     }
   }
 }
@@ -153,226 +229,352 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
 //     row-major; one super-block is one pass of the 256 CUs, so at any time the chip works on
 //     (16+16) x 256 rows of X, which the memory-side cache holds;
 //   * inside a super-block each XCD owns an 8 x 4 rectangle of tiles (12 row panels shared by its
-//     32 CUs through its own L2); the rectangle rotates with the super-block index so that
-//     partially empty (diagonal, ragged) super-blocks do not starve the same XCD every time;
-//   * workgroup w runs on XCD w % 8 (hardware round-robin, verified on device) and pops tiles of
-//     its XCD from a per-XCD counter, so imbalance inside an XCD is absorbed dynamically.
-// item t of XCD x  ->  tile (I, J) or "nothing here" (below the diagonal / outside the grid).
-__device__ __forceinline__ bool decode_item(const JoinArgs& a, uint32_t xcd, uint32_t t, uint32_t& I, uint32_t& J) {
-  const uint32_t sbi = t >> 5, slot = t & 31;
-  const uint32_t nsb = a.nsb;
-  // row-major upper triangle: row P starts at P*nsb - P(P-1)/2
-  const double b = 2.0 * nsb + 1.0;
-  uint32_t P = (uint32_t)((b - sqrt(b * b - 8.0 * (double)sbi)) * 0.5);
-  if (P >= nsb) P = nsb - 1;
-  auto start = [nsb](uint32_t p) { return (uint64_t)p * nsb - ((uint64_t)p * (p - 1)) / 2; };
-  while (P > 0 && start(P) > sbi) --P;
-  while (P + 1 < nsb && start(P + 1) <= sbi) ++P;
-  const uint32_t Q = P + (uint32_t)(sbi - start(P));
-  const uint32_t xp = (xcd + sbi) & 7;
-  I = P * SB + (xp >> 2) * 8 + (slot >> 2);
-  J = Q * SB + (xp & 3) * 4 + (slot & 3);
-  return I <= J && J < a.ntiles;
+//     32 CUs through its own L2); rectangle and slot rotate with the super-block index so that
+//     partially empty (diagonal, ragged) super-blocks do not idle the same workgroups every time;
+//   * workgroup w runs on XCD w % 8 (hardware round-robin, verified on device) and takes slot
+//     w / 8 of its XCD's rectangle in every super-block: a static schedule, no queue, no atomics.
+struct TileCursor {
+  uint32_t xcd, k, wpx;  // this workgroup: XCD, index within the XCD, workgroups per XCD
+  uint32_t nsb, ntiles;
+  uint32_t u;            // item index: super-block u / 32, slot u % 32
+  uint32_t P, Q, sbi;    // super-block coordinates (P <= Q) and linear index
+  uint64_t total_items;
+  __device__ void init(uint32_t block, uint32_t nblocks, uint32_t nsb_, uint32_t ntiles_) {
+    xcd = block % NUM_XCD;
+    k = block / NUM_XCD;
+    wpx = (nblocks - xcd + NUM_XCD - 1) / NUM_XCD;  // workgroups with this XCD id
+    nsb = nsb_;
+    ntiles = ntiles_;
+    total_items = (uint64_t)nsb * (nsb + 1) / 2 * 32;
+    u = k;
+    P = Q = sbi = 0;
+  }
+  // next non-empty tile of this workgroup, in order; false when the work is exhausted
+  __device__ bool next(uint32_t& I, uint32_t& J) {
+    while ((uint64_t)u < total_items) {
+      const uint32_t sb_want = u >> 5, slot0 = u & 31;
+      while (sbi < sb_want) {  // advance (P, Q) row-major over the upper triangle
+        ++sbi;
+        if (++Q == nsb) {
+          ++P;
+          Q = P;
+        }
+      }
+      const uint32_t xp = (xcd + sbi) & 7;
+      const uint32_t slot = (slot0 + 5 * sbi) & 31;
+      I = P * SB + (xp >> 2) * 8 + (slot >> 2);
+      J = Q * SB + (xp & 3) * 4 + (slot & 3);
+      u += wpx;
+      if (I <= J && J < ntiles) return true;
+    }
+    return false;
+  }
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else static_assert(N == 0, "unsupported count");
+}
+
+// Workgroup barrier without the fences of __syncthreads(): those make the compiler wait for every
+// outstanding global->LDS copy (vmcnt(0)) at each barrier, which would serialise the copy pipeline.
+// The kernel orders its LDS traffic itself: copies are certified with counted vmcnt waits before the
+// barrier, and fragment reads are complete once the MFMAs consuming them have issued.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// The augmentation rows of a wave tile: four A-side rows (32 rows = 512 B apart) and two B-side rows,
+// read with LDS instructions the compiler does not see as LDS accesses (it would otherwise wait for
+// all outstanding global->LDS copies first).  The wait is part of the same statement, so every use
+// of the results is ordered after it.
+__device__ __forceinline__ void lds_read_aux(uint32_t addr_a, uint32_t addr_b, uint4 (&ra)[4], uint4 (&rb)[2]) {
+  asm volatile(
+      "ds_read_b128 %0, %6\n\t"
+      "ds_read_b128 %1, %6 offset:512\n\t"
+      "ds_read_b128 %2, %6 offset:1024\n\t"
+      "ds_read_b128 %3, %6 offset:1536\n\t"
+      "ds_read_b128 %4, %7\n\t"
+      "ds_read_b128 %5, %7 offset:512\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(ra[0]), "=&v"(ra[1]), "=&v"(ra[2]), "=&v"(ra[3]), "=&v"(rb[0]), "=&v"(rb[1])
+      : "v"(addr_a), "v"(addr_b)
+      : "memory");
 }
 
 template <bool COUNT>
 __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if (*a.status != ST_OK) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int r32 = lane & 31, hi = lane >> 5;
-  const uint32_t xcd = blockIdx.x & (NUM_XCD - 1);
-  int4* slots = reinterpret_cast<int4*>(lds + SLOT_OFF);
+  const int nsl = a.nslices;
+  const int DIST = nsl < NSTAGE - 1 ? nsl : NSTAGE - 1;  // slices kept in flight
 
-  // thread 0 pops items of this XCD.  `resolve` turns a raw item into {I, J, valid, 0}, popping
-  // further items while they are empty (below the diagonal / outside the grid).
-  auto resolve = [&](uint32_t t) -> int4 {
-    for (;;) {
-      if (t >= a.items_per_xcd) return make_int4(0, 0, 0, 0);
-      uint32_t I, J;
-      if (decode_item(a, xcd, t, I, J)) return make_int4((int)I, (int)J, 1, 0);
-      t = atomicAdd(&a.queue[xcd], 1u);
-    }
-  };
+  reinterpret_cast<uint32_t*>(lds + ZERO_OFF)[tid] = 0;
+  static_assert(ZERO_BYTES == THREADS * 4, "one dword per thread");
 
-  // --- global->LDS copy addressing: wave w copies rows 8*(w + 8q) .. +7 (q = 0..3) of both panels;
-  // lane l handles row +l/8 and the LDS chunk position l%8, i.e. the logical chunk (l%8) ^ swz(row).
-  const int drow = lane >> 3;
+  // --- global->LDS copy addressing.  One global_load_lds_dwordx4 writes 1 KB of LDS = 16 rows of a
+  // panel; wave w copies row groups w and w + 8 of both panels.  Lane l handles row +l/4 and the
+  // LDS chunk position l%4, i.e. the logical chunk (l%4) ^ swz(row).
   const char* Xb = reinterpret_cast<const char*>(a.X);
   const int64_t rowbytes = a.ld * 2;
-  const char* gA[4];
-  const char* gB[4];
-  auto set_tile_ptrs = [&](int I, int J) {
+  const char* gA[2];
+  const char* gB[2];
+  auto set_tile_ptrs = [&](uint32_t I, uint32_t J) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = 8 * (wave + 8 * q) + drow;
-      const int chunk = (lane & 7) ^ swz(row);
+    for (int q = 0; q < 2; ++q) {
+      const int row = 16 * (wave + 8 * q) + (lane >> 2);
+      const int chunk = (lane & 3) ^ swz(row);
       int64_t ra = (int64_t)I * TILE + row, rb = (int64_t)J * TILE + row;
-      if (ra >= a.n) ra = a.n - 1;  // rows past the end are clamped; their results are masked by s = +inf
+      if (ra >= a.n) ra = a.n - 1;  // rows past the end are clamped; their pairs are masked by the augmentation row
       if (rb >= a.n) rb = a.n - 1;
       gA[q] = Xb + ra * rowbytes + chunk * 16;
       gB[q] = Xb + rb * rowbytes + chunk * 16;
     }
   };
-  auto issue_slice = [&](int ks, int stage) {
+  auto issue_slice = [&](int ks, uint32_t stage) {
     char* base = lds + stage * STAGE_BYTES;
+    const int64_t koff = (int64_t)ks * (KSLICE * 2);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      __builtin_amdgcn_global_load_lds(EJ_GLB(gA[q] + (int64_t)ks * (KSLICE * 2)), EJ_LDS(base + (wave + 8 * q) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(EJ_GLB(gB[q] + (int64_t)ks * (KSLICE * 2)),
-                                       EJ_LDS(base + PANEL_BYTES + (wave + 8 * q) * 1024), 16, 0, 0);
+    for (int q = 0; q < 2; ++q) {
+      __builtin_amdgcn_global_load_lds(EJ_GLB(gA[q] + koff), EJ_LDS(base + (wave + 8 * q) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(EJ_GLB(gB[q] + koff), EJ_LDS(base + PANEL_BYTES + (wave + 8 * q) * 1024), 16, 0, 0);
     }
   };
-  // norm of this thread's row (threads 0..255: rows of the tile, A side; 256..511: columns, B side);
-  // rows past the end get +inf, so none of their pairs can pass the filter
-  auto load_norm = [&](int I, int J) -> float {
+  // augmentation rows of the tile's 256 rows and 256 columns: 8 KB, copied with one more
+  // global_load_lds per wave (thread t fetches the row of point I*256+t, or J*256+t-256); H is padded to
+  // a multiple of the tile edge, so no clamping is needed
+  auto aux_buf = [&](uint32_t parity) -> uint4* { return reinterpret_cast<uint4*>(lds + AUX_OFF) + parity * (2 * TILE); };
+  auto issue_aux = [&](uint32_t I, uint32_t J, uint32_t parity) {
     const int64_t g = (tid < TILE) ? (int64_t)I * TILE + tid : (int64_t)J * TILE + (tid - TILE);
-    return (g < a.n) ? a.s[g] : __builtin_inff();
+    __builtin_amdgcn_global_load_lds(EJ_GLB(a.H + g), EJ_LDS(reinterpret_cast<char*>(aux_buf(parity)) + wave * 1024), 16, 0, 0);
   };
-  auto norm_buf = [&](int parity) -> float* { return reinterpret_cast<float*>(lds + NORM_OFF) + parity * (2 * TILE); };
 
-  // --- fragment read addressing (byte offsets inside a stage)
-  // A operand of v_mfma_f32_32x32x16_f16: lane l supplies row l%32, coordinates 8*(l/32) .. +7 of the 16-wide step.
-  int offA[4], offB[4];  // per 16-wide k step; m-tile / n-tile add 32 rows = 4096 B (swz unchanged: 32 % 16 == 0)
+  // --- fragment read addressing (byte offsets inside a stage).  A operand of
+  // v_mfma_f32_32x32x16_f16: lane l supplies row l%32, coordinates 8*(l/32) .. +7 of the 16-wide step.
+  // m-tile / n-tile t adds 32 rows = 2048 B (swz unchanged: 32 rows = 8 groups of 4).
+  int offA[2], offB[2];
   {
     const int rowA = wm * 128 + r32, rowB = wn * 64 + r32;
 #pragma unroll
-    for (int k16 = 0; k16 < 4; ++k16) {
-      offA[k16] = rowA * 128 + (((2 * k16 + hi) ^ swz(rowA)) << 4);
-      offB[k16] = PANEL_BYTES + rowB * 128 + (((2 * k16 + hi) ^ swz(rowB)) << 4);
+    for (int k16 = 0; k16 < 2; ++k16) {
+      offA[k16] = rowA * 64 + (((2 * k16 + hi) ^ swz(rowA)) << 4);
+      offB[k16] = PANEL_BYTES + rowB * 64 + (((2 * k16 + hi) ^ swz(rowB)) << 4);
     }
   }
+  auto load_frags = [&](uint32_t stage, int k16, half8 (&fa)[4], half8 (&fb)[2]) {
+    const char* st = lds + stage * STAGE_BYTES;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const half8*>(st + offA[k16] + mt * 2048);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) fb[nt] = *reinterpret_cast<const half8*>(st + offB[k16] + nt * 2048);
+  };
 
   float16v acc[4][2];
-
-  // ---------------- prologue: first tile
-  if (tid == 0) slots[0] = resolve(atomicAdd(&a.queue[xcd], 1u));
-  __syncthreads();
-  int4 cur = slots[0];
-  uint32_t T = 0;  // tiles done by this workgroup
-  uint32_t g = 0;  // k-slices done by this workgroup (stage = g & 1)
-  if (cur.z) {
-    norm_buf(0)[tid] = load_norm(cur.x, cur.y);
-    set_tile_ptrs(cur.x, cur.y);
-    issue_slice(0, 0);
-  }
-  uint32_t raw_next = 0;
-
-  while (cur.z) {
-    const int I = cur.x, J = cur.y;
-    int4 nxt = make_int4(0, 0, 0, 0);
-    float nxt_norm = 0.f;
+  auto mma_step = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
+      for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
+  };
+  auto mma_step_first = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
+    float16v z;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], z, 0, 0, 0);
+  };
 
-    for (int ks = 0; ks < a.nslices; ++ks, ++g) {
-      const bool last = (ks + 1 == a.nslices);
-      // one-tile lookahead: thread 0 publishes the tile after this one before the barrier of
-      // this tile's last slice (the raw item was popped a slice earlier, so its latency is hidden)
-      if (last && tid == 0) {
-        if (a.nslices == 1) raw_next = atomicAdd(&a.queue[xcd], 1u);
-        slots[(T + 1) & 1] = resolve(raw_next);
-      }
-      // this wave's copies of slice ks have landed; after the barrier everybody's have, and
-      // everybody is done reading the other stage (slice ks-1)
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (ks == 0 && a.nslices > 1 && tid == 0) raw_next = atomicAdd(&a.queue[xcd], 1u);
-      if (!last) {
-        issue_slice(ks + 1, (g + 1) & 1);
-      } else {
-        nxt = slots[(T + 1) & 1];
-        if (nxt.z) {
-          nxt_norm = load_norm(nxt.x, nxt.y);  // issued before the copies so that waiting for it does not wait for them
-          set_tile_ptrs(nxt.x, nxt.y);
-          issue_slice(0, (g + 1) & 1);
-        }
-      }
-      const char* st = lds + (g & 1) * STAGE_BYTES;
-#pragma unroll
-      for (int k16 = 0; k16 < 4; ++k16) {
-        half8 fa[4], fb[2];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const half8*>(st + offA[k16] + mt * 4096);
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) fb[nt] = *reinterpret_cast<const half8*>(st + offB[k16] + nt * 4096);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
+  // --- per-wave result staging (pair mode): entries are appended in LDS and written out in bulk
+  // with one atomic per flush (wavefront ballot + prefix ranks + one atomic per wavefront flush).
+  uint32_t* stg = reinterpret_cast<uint32_t*>(lds + STG_OFF + wave * STG_WAVE_BYTES);
+  uint32_t fill = 0;               // wave-uniform
+  unsigned long long hits = 0;     // count mode: pairs found by this wave
+  bool dirty = false;              // stores/atomics issued since the last vmcnt(0): counted waits are unsafe
+  auto flush = [&]() {
+    if (fill == 0) return;
+    unsigned long long base = 0;
+    if (lane == 0) base = atomicAdd(a.n_pairs, (unsigned long long)fill);
+    const uint32_t blo = __builtin_amdgcn_readfirstlane((uint32_t)base);
+    const uint32_t bhi = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+    base = ((unsigned long long)bhi << 32) | blo;
+    for (uint32_t e = lane; e < fill; e += 64) {
+      const unsigned long long idx = base + e;
+      if (idx < a.capacity) {
+        reinterpret_cast<uint2*>(a.pairs)[idx] = make_uint2(stg[3 * e], stg[3 * e + 1]);
+        if (a.dist2) a.dist2[idx] = __uint_as_float(stg[3 * e + 2]);
       }
     }
-    // norms of the next tile go to the other parity's staging area; its last readers (epilogue of
-    // tile T-1) are behind every wave that has passed this tile's first barrier
-    if (nxt.z) norm_buf((T + 1) & 1)[tid] = nxt_norm;
+    fill = 0;
+    dirty = true;
+  };
 
-    // ---------------- epilogue (Step 3 of Section 3.1 + the epsilon filter), fused
-    // accumulator register r of tile (mt, nt) in lane l is the pair
-    //   i = I*256 + wm*128 + mt*32 + 8*(r/4) + 4*(l/32) + r%4 ,  j = J*256 + wn*64 + nt*32 + l%32.
+  // ---------------- prologue
+  TileCursor tc;
+  tc.init(blockIdx.x, gridDim.x, a.nsb, a.ntiles);
+  uint32_t I = 0, J = 0, In = 0, Jn = 0;
+  bool have = tc.next(I, J);
+  if (!have) return;
+  bool have_next = tc.next(In, Jn);
+  uint32_t T = 0;   // tiles done by this workgroup
+  uint32_t G = 0;   // slices computed so far (stage = G % NSTAGE)
+  uint32_t Gi = 0;  // slices issued so far
+  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` of the current tile,
+  // or, once that tile is fully issued, of the next one.  The first slice of a tile carries the
+  // tile's augmentation rows as a fifth copy instruction, issued first.
+  int iks = 0;
+  bool issue_on_next = false;
+  bool issue_valid = true;
+  uint32_t young5 = 0;  // bit (Gi-1-g) & 1 ... : whether the most recently issued slice had 5 copies
+  set_tile_ptrs(I, J);
+  auto issue_one = [&]() {
+    if (!issue_valid) return;
+    young5 = (iks == 0);
+    if (iks == 0) {
+      if (issue_on_next) issue_aux(In, Jn, (T + 1) & 1); else issue_aux(I, J, T & 1);
+    }
+    issue_slice(iks, Gi % NSTAGE);
+    ++Gi;
+    if (++iks == nsl) {
+      iks = 0;
+      if (!issue_on_next && have_next) {
+        issue_on_next = true;
+        set_tile_ptrs(In, Jn);
+      } else {
+        issue_valid = false;
+      }
+    }
+  };
+  for (int q = 0; q < DIST; ++q) issue_one();
+  // slice 0 (and the augmentation rows) have landed when only the DIST-1 younger slices' copies
+  // (4 per slice and wave) are outstanding
+  if (DIST == 3) wait_vmcnt<8>(); else if (DIST == 2) wait_vmcnt<4>(); else wait_vmcnt<0>();
+  __syncthreads();
+  half8 fa0[4], fb0[2], fa1[4], fb1[2];
+  load_frags(0, 0, fa0, fb0);
+
+  while (have) {
+    for (int ks = 0; ks < nsl; ++ks, ++G) {
+      // (a) this wave's copies of slice G+1 have landed once only the younger slice's copies are outstanding
+      {
+        const bool younger = Gi > G + 2;  // at most one younger slice (DIST <= 3)
+        if (dirty || !younger) { wait_vmcnt<0>(); dirty = false; }
+        else if (young5) wait_vmcnt<5>();
+        else wait_vmcnt<4>();
+      }
+      // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
+      wg_barrier();
+      // (c) refill the stage slice G-1 occupied
+      if (Gi < G + 1 + DIST) issue_one();
+      // (d) slice G: two 16-wide steps; the first step's fragments were read before the barrier
+      load_frags(G % NSTAGE, 1, fa1, fb1);
+      if (ks == 0) mma_step_first(fa0, fb0); else mma_step(fa0, fb0);
+      load_frags((G + 1) % NSTAGE, 0, fa0, fb0);  // slice G+1 was certified by barrier (b)
+      mma_step(fa1, fb1);
+    }
+
+    // ---------------- epilogue: the augmentation step, then the filter
     {
-      const float* nb = norm_buf(T & 1);
+      // lanes 32..63 supply coordinates 8..15 of the step, which are zero
+      const uint32_t ab = (uint32_t)(uintptr_t)aux_buf(T & 1);
+      const uint32_t zero = (uint32_t)(uintptr_t)(lds + ZERO_OFF);
+      uint4 ra[4], rb[2];
+      lds_read_aux(hi ? zero : ab + (wm * 128 + r32) * 16, hi ? zero : ab + (TILE + wn * 64 + r32) * 16, ra, rb);
+      half8 ha[4], hb[2];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) ha[mt] = as_half8(ra[mt]);
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) hb[nt] = as_half8(make_uint4(rb[nt].z, rb[nt].w, rb[nt].x, rb[nt].y));
+      mma_step(ha, hb);
+      // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of tile (mt, nt) in lane l is the pair
+      //   i = I*256 + wm*128 + mt*32 + 8*(r/4) + 4*(l/32) + r%4 ,  j = J*256 + wn*64 + nt*32 + l%32.
       const bool diag = (I == J);
-      const uint32_t ibase = (uint32_t)I * TILE + wm * 128 + 4 * hi;
-      const uint32_t jbase = (uint32_t)J * TILE + wn * 64 + r32;
-      unsigned long long wave_hits = 0;
       // a wave tile of a diagonal block that lies entirely below the diagonal holds no pair i <= j
       const bool skip = diag && (wm * 128 >= wn * 64 + 64);
+      // cheap filter: which of the eight 32 x 32 blocks of this wave tile hold a passing pair at all
+      uint32_t blocks_hit = 0;
       if (!skip) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          const float sj = nb[TILE + wn * 64 + nt * 32 + r32];
-          const uint32_t j = jbase + nt * 32;
+        for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) {
+          for (int nt = 0; nt < 2; ++nt) {
+            const float16v& v = acc[mt][nt];
+            float m = fmaxf(fmaxf(v[0], v[1]), v[2]);
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-              const float4v si4 = *reinterpret_cast<const float4v*>(nb + wm * 128 + mt * 32 + 8 * rq + 4 * hi);
+            for (int r = 3; r < 15; r += 2) m = fmaxf(fmaxf(m, v[r]), v[r + 1]);
+            m = fmaxf(m, v[15]);
+            if (__ballot(m >= a.thr)) blocks_hit |= 1u << (mt * 2 + nt);
+          }
+        }
+      }
+      // rare path, one block at a time
+      while (blocks_hit) {
+        const int b = __builtin_ctz(blocks_hit);
+        blocks_hit &= blocks_hit - 1;
+        float16v v;
+        switch (b) {
+          case 0: v = acc[0][0]; break;
+          case 1: v = acc[0][1]; break;
+          case 2: v = acc[1][0]; break;
+          case 3: v = acc[1][1]; break;
+          case 4: v = acc[2][0]; break;
+          case 5: v = acc[2][1]; break;
+          case 6: v = acc[3][0]; break;
+          default: v = acc[3][1]; break;
+        }
+        const int mt = b >> 1, nt = b & 1;
+        const uint32_t nn = (uint32_t)a.n;
+        const uint32_t j = J * TILE + wn * 64 + nt * 32 + r32;
+        const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
 #pragma unroll
-              for (int rr = 0; rr < 4; ++rr) {
-                const float d2 = fmaf(-2.f, acc[mt][nt][4 * rq + rr], si4[rr] + sj);
-                const uint32_t i = ibase + mt * 32 + 8 * rq + rr;
-                bool pass = d2 <= a.eps2;  // rows/columns past n carry s = +inf and never pass
-                if (diag) pass = (i == j) ? (COUNT ? false : (i < a.n)) : (pass && i < j);
-                const unsigned long long mask = __ballot(pass);
-                if (mask) {
-                  const uint32_t cnt = __popcll(mask);
-                  if (COUNT) {
-                    if (pass) {
-                      atomicAdd(&a.counts[i], 1u);
-                      atomicAdd(&a.counts[j], 1u);
-                    }
-                    wave_hits += cnt;
-                  } else {
-                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                    unsigned long long base = 0;
-                    if (rank == 0 && pass) base = atomicAdd(a.n_pairs, (unsigned long long)cnt);
-                    // broadcast from the first passing lane
-                    const int src = __ffsll((long long)mask) - 1;
-                    const uint32_t blo = __builtin_amdgcn_readlane((uint32_t)base, src);
-                    const uint32_t bhi = __builtin_amdgcn_readlane((uint32_t)(base >> 32), src);
-                    base = ((unsigned long long)bhi << 32) | blo;
-                    const unsigned long long idx = base + rank;
-                    if (pass && idx < a.capacity) {
-                      reinterpret_cast<uint2*>(a.pairs)[idx] = make_uint2(i, j);
-                      if (a.dist2) a.dist2[idx] = (i == j) ? 0.f : fmaxf(d2, 0.f);
-                    }
-                  }
-                }
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
+          // rows/columns past n carry a large negative marker, which a huge epsilon can still reach: mask them here
+          bool pass = v[r] >= a.thr && i < nn && j < nn;
+          if (diag) pass = pass && (COUNT ? i < j : i <= j);
+          const unsigned long long mask = __ballot(pass);
+          if (mask) {
+            const uint32_t cnt = __popcll(mask);
+            if (COUNT) {
+              if (pass) {
+                atomicAdd(&a.counts[i], 1u);
+                atomicAdd(&a.counts[j], 1u);
               }
+              hits += cnt;
+              dirty = true;
+            } else {
+              if (fill + cnt > STG_CAP) flush();
+              const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+              if (pass) {
+                const uint32_t e = fill + rank;
+                stg[3 * e] = i;
+                stg[3 * e + 1] = j;
+                stg[3 * e + 2] = __float_as_uint(fmaxf(-2.f * v[r], 0.f));
+              }
+              fill += cnt;
             }
           }
         }
       }
-      if (COUNT && wave_hits && lane == 0) atomicAdd(a.total, wave_hits);
     }
-    cur = nxt;
+    I = In;
+    J = Jn;
+    have = have_next;
+    if (have) {
+      have_next = tc.next(In, Jn);
+      issue_on_next = false;  // the issue cursor, if it had moved on, is now on the current tile
+    }
     ++T;
   }
+  if (!COUNT) flush();
+  if (COUNT && hits && lane == 0) atomicAdd(a.total, hits);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -383,9 +585,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 struct ejoin_ctx {
   int device;
   int num_cu;
-  uint32_t* queue;              // NUM_XCD counters
-  unsigned long long* scratch;  // 2 x u64 (unused outputs land here)
-  float* s;                     // norms workspace
+  uint32_t* status;  // device: [0] status word, [1] max norm bits
+  float* s;          // workspace: norms (4 B per point)
+  uint4* H;          // workspace: augmentation rows (16 B per point)
   int64_t s_cap;
   int profiling;
   hipEvent_t ev[4];
@@ -411,35 +613,53 @@ int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int6
   if (!ctx || !X) return EJOIN_EINVAL;
   if (n < 1 || n >= (int64_t)0xFFFFFFFFll - TILE) return EJOIN_EINVAL;
   if (d < 1 || d > 65536) return EJOIN_EINVAL;
-  const int64_t dk = ((int64_t)d + KSLICE - 1) / KSLICE * KSLICE;
-  if (ld < dk || (ld % KSLICE) != 0) return EJOIN_EINVAL;
+  const int64_t dk = ((int64_t)d + KPAD - 1) / KPAD * KPAD;
+  if (ld < dk || (ld % KPAD) != 0) return EJOIN_EINVAL;
   if ((reinterpret_cast<uintptr_t>(X) & 127) != 0) return EJOIN_EINVAL;
   return EJOIN_OK;
 }
 
 int ensure_workspace(ejoin_ctx* ctx, int64_t n) {
   if (n <= ctx->s_cap) return EJOIN_OK;
-  if (ctx->s) {
+  if (ctx->s || ctx->H) {
     EJ_TRY(hipDeviceSynchronize());
-    EJ_TRY(hipFree(ctx->s));
+    if (ctx->s) EJ_TRY(hipFree(ctx->s));
     ctx->s = nullptr;
+    if (ctx->H) EJ_TRY(hipFree(ctx->H));
+    ctx->H = nullptr;
     ctx->s_cap = 0;
   }
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->s), (size_t)n * sizeof(float));
-  if (e == hipErrorOutOfMemory) {
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->H), (size_t)((n + TILE - 1) / TILE * TILE) * sizeof(uint4));
+  if (e != hipSuccess) {
     (void)hipGetLastError();
-    return EJOIN_ENOMEM;
+    if (ctx->s) (void)hipFree(ctx->s);
+    ctx->s = nullptr;
+    if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
+    return fail_hip(ctx, e, "hipMalloc(workspace)");
   }
-  if (e != hipSuccess) return fail_hip(ctx, e, "hipMalloc(norm workspace)");
   ctx->s_cap = n;
   return EJOIN_OK;
 }
 
-int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, hipStream_t st) {
-  const int k16 = (d + KSLICE - 1) / KSLICE * (KSLICE / 16);
+int k16_steps(int32_t d) { return (d + KPAD - 1) / KPAD * (KPAD / 16); }
+
+int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, uint32_t* max_bits, hipStream_t st) {
   const int64_t waves = (n + 31) / 32;
   const unsigned blocks = (unsigned)((waves + 3) / 4);
-  hipLaunchKernelGGL(k_norms, dim3(blocks), dim3(256), 0, st, X, n, ld, k16, s);
+  hipLaunchKernelGGL(k_norms, dim3(blocks), dim3(256), 0, st, X, n, ld, k16_steps(d), s, max_bits);
+  EJ_TRY(hipGetLastError());
+  return EJOIN_OK;
+}
+
+// Steps shared by the join and the dense-tile call: reset, norms (+ max), augmentation rows.
+int launch_prepare(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, unsigned long long* counter, hipStream_t st) {
+  hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctx->status, counter);
+  EJ_TRY(hipGetLastError());
+  int rc = launch_norms(ctx, X, n, d, ld, ctx->s, ctx->status + 1, st);
+  if (rc != EJOIN_OK) return rc;
+  const int64_t npad = (n + TILE - 1) / TILE * TILE;
+  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, ctx->s, n, npad, ctx->status, ctx->H);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -465,17 +685,14 @@ int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld
   JoinArgs a;
   memset(&a, 0, sizeof(a));
   a.X = X;
-  a.s = ctx->s;
+  a.H = ctx->H;
+  a.status = ctx->status;
   a.n = n;
   a.ld = ld;
-  a.nslices = (d + KSLICE - 1) / KSLICE;
-  a.eps2 = eps * eps;
+  a.nslices = (d + KPAD - 1) / KPAD * (KPAD / KSLICE);
+  a.thr = -0.5f * (eps * eps);
   a.ntiles = (uint32_t)((n + TILE - 1) / TILE);
   a.nsb = (a.ntiles + SB - 1) / SB;
-  const uint64_t items = (uint64_t)a.nsb * (a.nsb + 1) / 2 * 32;
-  if (items >= 0xFFFFFFFFull - 4096) return EJOIN_EUNSUPPORTED;
-  a.items_per_xcd = (uint32_t)items;
-  a.queue = ctx->queue;
   a.pairs = pairs;
   a.dist2 = dist2;
   a.capacity = capacity;
@@ -484,16 +701,16 @@ int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld
   a.total = reinterpret_cast<unsigned long long*>(total);
 
   if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
-  rc = launch_norms(ctx, X, n, d, ld, ctx->s, st);
+  rc = launch_prepare(ctx, X, n, d, ld, COUNT ? a.total : a.n_pairs, st);
   if (rc != EJOIN_OK) return rc;
-  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[1], st));
-  hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctx->queue, COUNT ? a.total : a.n_pairs, (unsigned long long*)nullptr);
-  EJ_TRY(hipGetLastError());
   if (COUNT) {
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counts, n, 0u);
     EJ_TRY(hipGetLastError());
   }
-  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[2], st));
+  if (ctx->profiling) {
+    EJ_TRY(hipEventRecord(ctx->ev[1], st));
+    EJ_TRY(hipEventRecord(ctx->ev[2], st));
+  }
   hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
   EJ_TRY(hipGetLastError());
   if (ctx->profiling) {
@@ -531,8 +748,8 @@ int ejoin_create(ejoin_ctx** out, int device) {
     delete ctx;
     return EJOIN_EHIP;
   }
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->queue), 256);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->scratch), 256);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->status), 256);
+  if (e == hipSuccess) e = hipMemset(ctx->status, 0, 256);
   for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&ctx->ev[i]);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -548,9 +765,9 @@ int ejoin_create(ejoin_ctx** out, int device) {
 int ejoin_destroy(ejoin_ctx* ctx) {
   if (!ctx) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
-  if (ctx->queue) (void)hipFree(ctx->queue);
-  if (ctx->scratch) (void)hipFree(ctx->scratch);
+  if (ctx->status) (void)hipFree(ctx->status);
   if (ctx->s) (void)hipFree(ctx->s);
+  if (ctx->H) (void)hipFree(ctx->H);
   for (int i = 0; i < 4; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
   delete ctx;
@@ -570,7 +787,7 @@ const char* ejoin_strerror(int code) {
     case EJOIN_EINVAL: return "invalid argument (null pointer, size out of range, ld not a multiple of 64 or < roundup(d,64), X not 128-byte aligned)";
     case EJOIN_EUNSUPPORTED: return "unsupported device (gfx950 required) or problem size";
     case EJOIN_EHIP: return "HIP runtime error (see ejoin_last_hip_error)";
-    case EJOIN_ENOMEM: return "out of device memory for the norm workspace";
+    case EJOIN_ENOMEM: return "out of device memory for the workspace (20 bytes per point)";
     default: return "unknown error code";
   }
 }
@@ -583,7 +800,7 @@ int ejoin_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t
   if (!s) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return launch_norms(ctx, X, n, d, ld, s, static_cast<hipStream_t>(stream));
+  return launch_norms(ctx, X, n, d, ld, s, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* counts,
@@ -617,11 +834,20 @@ int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   rc = ensure_workspace(ctx, n);
   if (rc != EJOIN_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  rc = launch_norms(ctx, X, n, d, ld, ctx->s, st);
+  rc = launch_prepare(ctx, X, n, d, ld, nullptr, st);
   if (rc != EJOIN_OK) return rc;
-  const int k16 = (d + KSLICE - 1) / KSLICE * (KSLICE / 16);
-  hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->s, n, ld, k16, i0, j0, rows, cols, out);
+  hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->H, ctx->status, n, ld, k16_steps(d), i0, j0, rows, cols, out);
   EJ_TRY(hipGetLastError());
+  return EJOIN_OK;
+}
+
+int ejoin_status(ejoin_ctx* ctx, int* status) {
+  if (!ctx || !status) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  uint32_t st = 0;
+  EJ_TRY(hipMemcpy(&st, ctx->status, sizeof(st), hipMemcpyDeviceToHost));
+  *status = (int)st;
   return EJOIN_OK;
 }
 
