@@ -76,7 +76,7 @@ def main():
     X = datagen.generate(w, n=n)
     Xd = torch.from_numpy(X.view(np.int16)).to("cuda:0")
     ej = pkg.EJoin(0)
-    ej.reserve(n)
+    ej.reserve(n, d)
     expect_pairs = int(n * (S / 2 * (n / spec["n"]) + 1))
     capacity = int(expect_pairs * 1.5) + (1 << 20)
     if args.mode == "pairs":

@@ -50,15 +50,16 @@ extern "C" {
 typedef struct ejoin_ctx ejoin_ctx;
 
 /* Create a context on HIP device `device`.  The context owns a few hundred bytes of device
- * status words and a workspace of 20 bytes per point (the norms s_i and their FP16 split; grown on
- * demand by the join calls with hipMalloc, or ahead of time by ejoin_reserve).  Host pointer out. */
+ * status words and a workspace: 20 bytes per point (the norms s_i and their FP16 split) plus, for
+ * the join calls, a re-laid-out copy of X (roundup(n,256) * roundup(d,64) * 2 bytes).  The workspace
+ * is grown on demand with hipMalloc, or ahead of time by ejoin_reserve.  Host pointer out. */
 int ejoin_create(ejoin_ctx** out, int device);
 
 /* Free the context and its device memory.  The caller must have synchronised its streams. */
 int ejoin_destroy(ejoin_ctx* ctx);
 
-/* Grow the workspace so that joins of up to n points allocate nothing. */
-int ejoin_reserve(ejoin_ctx* ctx, int64_t n);
+/* Grow the workspace so that joins of up to n points of up to d coordinates allocate nothing. */
+int ejoin_reserve(ejoin_ctx* ctx, int64_t n, int32_t d);
 
 /* Static, human-readable text for a return code. */
 const char* ejoin_strerror(int code);

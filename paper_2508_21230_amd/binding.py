@@ -35,7 +35,7 @@ def load_library() -> C.CDLL:
     lib.ejoin_destroy.restype = C.c_int
     lib.ejoin_destroy.argtypes = [vp]
     lib.ejoin_reserve.restype = C.c_int
-    lib.ejoin_reserve.argtypes = [vp, i64]
+    lib.ejoin_reserve.argtypes = [vp, i64, i32]
     lib.ejoin_strerror.restype = C.c_char_p
     lib.ejoin_strerror.argtypes = [C.c_int]
     lib.ejoin_last_hip_error.restype = C.c_char_p
@@ -48,6 +48,8 @@ def load_library() -> C.CDLL:
     lib.ejoin_selfjoin_pairs.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
     lib.ejoin_dist2_tile.restype = C.c_int
     lib.ejoin_dist2_tile.argtypes = [vp, vp, i64, i32, i64, i64, i64, i32, i32, vp, vp]
+    lib.ejoin_status.restype = C.c_int
+    lib.ejoin_status.argtypes = [vp, C.POINTER(C.c_int)]
     lib.ejoin_set_profiling.restype = C.c_int
     lib.ejoin_set_profiling.argtypes = [vp, C.c_int]
     lib.ejoin_last_kernel_ms.restype = C.c_int
@@ -105,8 +107,8 @@ class EJoin:
         d = width if d is None else int(d)
         return n, d, ld
 
-    def reserve(self, n: int):
-        self._check(self._lib.ejoin_reserve(self._h, int(n)), self._h)
+    def reserve(self, n: int, d: int):
+        self._check(self._lib.ejoin_reserve(self._h, int(n), int(d)), self._h)
 
     def norms(self, X: torch.Tensor, d: int | None = None) -> torch.Tensor:
         n, d, ld = self._x(X, d)
@@ -149,6 +151,12 @@ class EJoin:
         self._check(self._lib.ejoin_dist2_tile(self._h, X.data_ptr(), n, d, ld, int(i0), int(j0), int(rows), int(cols),
                                                out.data_ptr(), self._stream()), self._h)
         return out
+
+    def status(self) -> int:
+        """Device status of the last join / dense-tile call (0 = ok); synchronises."""
+        st = C.c_int()
+        self._check(self._lib.ejoin_status(self._h, C.byref(st)), self._h)
+        return int(st.value)
 
     def set_profiling(self, on: bool):
         self._check(self._lib.ejoin_set_profiling(self._h, 1 if on else 0), self._h)

@@ -56,11 +56,11 @@ constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
 __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
 struct JoinArgs {
-  const uint16_t* X;
+  const uint4* Xp;         // packed copy of X, see k_pack
+  int64_t npad;            // rows of Xp per k-block: n rounded up to a multiple of TILE
   const uint4* H;          // per point: the 16-byte augmentation row, see k_aux
   const uint32_t* status;  // device status word
   int64_t n;
-  int64_t ld;
   int nslices;  // roundup(d, 64) / 32
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntiles;  // ceil(n / TILE)
@@ -188,6 +188,25 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
 
 __device__ __forceinline__ half8 as_half8(uint4 v) { return __builtin_bit_cast(half8, v); }
 
+// Packed copy of X for the join kernel.  Xp is cut into k-blocks of 32 coordinates; block kb holds,
+// for every row r < npad, the row's four 16-byte chunks of that block, already permuted the way
+// the LDS wants them (chunk c at position c ^ swz(r)); rows n .. npad-1 are zero.  In this layout a
+// 256-row panel of one k-block is 16 KB of contiguous memory, so the global->LDS copies are straight
+// 1 KB block copies made of full 128-byte lines (in the row-major X a 32-coordinate slice of a row is
+// half a line, and the L2 would be asked for every line twice).
+// Thread t writes chunk t of Xp (fully coalesced writes; reads are 64-byte segments).
+__global__ void k_pack(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int nkb, uint4* __restrict__ Xp) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)nkb * npad * 4;
+  if (t >= total) return;
+  const int p = (int)(t & 3);
+  const int64_t rk = t >> 2;
+  const int64_t kb = rk / npad, r = rk - kb * npad;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (r < n) v = *reinterpret_cast<const uint4*>(X + r * ld + kb * KSLICE + ((p ^ swz((int)(r & 255))) << 3));
+  Xp[t] = v;
+}
+
 // Dense block of squared distances with the join's arithmetic: one wavefront per 32 x 32 block.
 __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ H,
                                                   const uint32_t* __restrict__ status, int64_t n, int64_t ld, int k16steps,
@@ -286,6 +305,21 @@ __device__ __forceinline__ void wait_vmcnt() {
 // barrier, and fragment reads are complete once the MFMAs consuming them have issued.
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// One global->LDS copy instruction: every lane moves 16 bytes from sbase + voff (sbase uniform) to
+// LDS address lds_addr + 16 * lane (lds_addr uniform, goes through M0).  Written as inline assembly
+// on purpose: for the builtin form the compiler assumes the instruction may also count on lgkmcnt,
+// and from then on turns every LDS wait into lgkmcnt(0), which breaks the overlap of fragment reads
+// with MFMAs.  The copies are tracked by hand with counted vmcnt waits (wait_vmcnt).
+__device__ __forceinline__ void copy16_to_lds(uint32_t lds_addr, const void* sbase, uint32_t voff) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_addr), "v"(voff), "s"(sbase)
+      : "memory", "m0");
+}
+
 // The augmentation rows of a wave tile: four A-side rows (32 rows = 512 B apart) and two B-side rows,
 // read with LDS instructions the compiler does not see as LDS accesses (it would otherwise wait for
 // all outstanding global->LDS copies first).  The wait is part of the same statement, so every use
@@ -318,41 +352,29 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   reinterpret_cast<uint32_t*>(lds + ZERO_OFF)[tid] = 0;
   static_assert(ZERO_BYTES == THREADS * 4, "one dword per thread");
 
-  // --- global->LDS copy addressing.  One global_load_lds_dwordx4 writes 1 KB of LDS = 16 rows of a
-  // panel; wave w copies row groups w and w + 8 of both panels.  Lane l handles row +l/4 and the
-  // LDS chunk position l%4, i.e. the logical chunk (l%4) ^ swz(row).
-  const char* Xb = reinterpret_cast<const char*>(a.X);
-  const int64_t rowbytes = a.ld * 2;
-  const char* gA[2];
-  const char* gB[2];
-  auto set_tile_ptrs = [&](uint32_t I, uint32_t J) {
+  // --- global->LDS copies.  One global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 B) = 16 rows of a
+  // panel; in the packed layout that is 1 KB of contiguous global memory.  Wave w copies blocks w and
+  // w + 8 of both 16 KB panels of a slice.  pa / pb: the panels' global addresses (uniform).
+  const char* Xb = reinterpret_cast<const char*>(a.Xp);
+  const int64_t kstride = a.npad * 64;  // bytes from one k-block of Xp to the next
+  const uint32_t lane16 = lane * 16;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+  auto issue_slice = [&](const char* pa, const char* pb, uint32_t stage) {
+    const uint32_t base = lds0 + stage * STAGE_BYTES;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int row = 16 * (wave + 8 * q) + (lane >> 2);
-      const int chunk = (lane & 3) ^ swz(row);
-      int64_t ra = (int64_t)I * TILE + row, rb = (int64_t)J * TILE + row;
-      if (ra >= a.n) ra = a.n - 1;  // rows past the end are clamped; their pairs are masked by the augmentation row
-      if (rb >= a.n) rb = a.n - 1;
-      gA[q] = Xb + ra * rowbytes + chunk * 16;
-      gB[q] = Xb + rb * rowbytes + chunk * 16;
+      const uint32_t blk = (wave + 8 * q) * 1024;
+      copy16_to_lds(base + blk, pa + blk, lane16);
+      copy16_to_lds(base + PANEL_BYTES + blk, pb + blk, lane16);
     }
   };
-  auto issue_slice = [&](int ks, uint32_t stage) {
-    char* base = lds + stage * STAGE_BYTES;
-    const int64_t koff = (int64_t)ks * (KSLICE * 2);
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      __builtin_amdgcn_global_load_lds(EJ_GLB(gA[q] + koff), EJ_LDS(base + (wave + 8 * q) * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(EJ_GLB(gB[q] + koff), EJ_LDS(base + PANEL_BYTES + (wave + 8 * q) * 1024), 16, 0, 0);
-    }
-  };
-  // augmentation rows of the tile's 256 rows and 256 columns: 8 KB, copied with one more
-  // global_load_lds per wave (thread t fetches the row of point I*256+t, or J*256+t-256); H is padded to
-  // a multiple of the tile edge, so no clamping is needed
+  // augmentation rows of the tile's 256 rows and 256 columns: 8 KB, copied with one more instruction
+  // per wave (waves 0..3: rows I*256 + 64*wave .. +63; waves 4..7: the columns); H is padded to a
+  // multiple of the tile edge, so no clamping is needed
   auto aux_buf = [&](uint32_t parity) -> uint4* { return reinterpret_cast<uint4*>(lds + AUX_OFF) + parity * (2 * TILE); };
   auto issue_aux = [&](uint32_t I, uint32_t J, uint32_t parity) {
-    const int64_t g = (tid < TILE) ? (int64_t)I * TILE + tid : (int64_t)J * TILE + (tid - TILE);
-    __builtin_amdgcn_global_load_lds(EJ_GLB(a.H + g), EJ_LDS(reinterpret_cast<char*>(aux_buf(parity)) + wave * 1024), 16, 0, 0);
+    const int64_t g0 = (int64_t)(wave < 4 ? I : J) * TILE + (wave & 3) * 64;
+    copy16_to_lds(lds0 + AUX_OFF + parity * (2 * TILE * 16) + wave * 1024, a.H + g0, lane16);
   };
 
   // --- fragment read addressing (byte offsets inside a stage).  A operand of
@@ -376,13 +398,16 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   };
 
   float16v acc[4][2];
-  auto mma_step = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
+  // One 16-wide step: the eight MFMAs of the wave tile on fragments (fa, fb), while the fragments of
+  // the following step (na, nb) are read from LDS.  The scheduling hints spread the six LDS reads
+  // between the first MFMAs, so that they complete under the remaining ones.
+  auto mma_only = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
   };
-  auto mma_step_first = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
+  auto mma_first = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
     float16v z;
 #pragma unroll
     for (int r = 0; r < 16; ++r) z[r] = 0.f;
@@ -391,7 +416,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], z, 0, 0, 0);
   };
-
+  auto interleave_hint = [&]() {
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  };
   // --- per-wave result staging (pair mode): entries are appended in LDS and written out in bulk
   // with one atomic per flush (wavefront ballot + prefix ranks + one atomic per wavefront flush).
   uint32_t* stg = reinterpret_cast<uint32_t*>(lds + STG_OFF + wave * STG_WAVE_BYTES);
@@ -432,21 +464,25 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   int iks = 0;
   bool issue_on_next = false;
   bool issue_valid = true;
-  uint32_t young5 = 0;  // bit (Gi-1-g) & 1 ... : whether the most recently issued slice had 5 copies
-  set_tile_ptrs(I, J);
+  bool young5 = false;  // the most recently issued slice had 5 copies
+  const char* pa = Xb + (int64_t)I * (TILE * 64);
+  const char* pb = Xb + (int64_t)J * (TILE * 64);
   auto issue_one = [&]() {
     if (!issue_valid) return;
     young5 = (iks == 0);
     if (iks == 0) {
       if (issue_on_next) issue_aux(In, Jn, (T + 1) & 1); else issue_aux(I, J, T & 1);
     }
-    issue_slice(iks, Gi % NSTAGE);
+    issue_slice(pa, pb, Gi % NSTAGE);
     ++Gi;
+    pa += kstride;
+    pb += kstride;
     if (++iks == nsl) {
       iks = 0;
       if (!issue_on_next && have_next) {
         issue_on_next = true;
-        set_tile_ptrs(In, Jn);
+        pa = Xb + (int64_t)In * (TILE * 64);
+        pb = Xb + (int64_t)Jn * (TILE * 64);
       } else {
         issue_valid = false;
       }
@@ -473,11 +509,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       wg_barrier();
       // (c) refill the stage slice G-1 occupied
       if (Gi < G + 1 + DIST) issue_one();
-      // (d) slice G: two 16-wide steps; the first step's fragments were read before the barrier
+      // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
+      //     (the second one reads from slice G+1, which barrier (b) has certified)
       load_frags(G % NSTAGE, 1, fa1, fb1);
-      if (ks == 0) mma_step_first(fa0, fb0); else mma_step(fa0, fb0);
-      load_frags((G + 1) % NSTAGE, 0, fa0, fb0);  // slice G+1 was certified by barrier (b)
-      mma_step(fa1, fb1);
+      if (ks == 0) mma_first(fa0, fb0); else mma_only(fa0, fb0);
+      interleave_hint();
+      load_frags((G + 1) % NSTAGE, 0, fa0, fb0);
+      mma_only(fa1, fb1);
+      interleave_hint();
     }
 
     // ---------------- epilogue: the augmentation step, then the filter
@@ -492,7 +531,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       for (int mt = 0; mt < 4; ++mt) ha[mt] = as_half8(ra[mt]);
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) hb[nt] = as_half8(make_uint4(rb[nt].z, rb[nt].w, rb[nt].x, rb[nt].y));
-      mma_step(ha, hb);
+      mma_only(ha, hb);
       // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of tile (mt, nt) in lane l is the pair
       //   i = I*256 + wm*128 + mt*32 + 8*(r/4) + 4*(l/32) + r%4 ,  j = J*256 + wn*64 + nt*32 + l%32.
       const bool diag = (I == J);
@@ -587,8 +626,10 @@ struct ejoin_ctx {
   int num_cu;
   uint32_t* status;  // device: [0] status word, [1] max norm bits
   float* s;          // workspace: norms (4 B per point)
-  uint4* H;          // workspace: augmentation rows (16 B per point)
-  int64_t s_cap;
+  uint4* H;          // workspace: augmentation rows (16 B per point, padded to a multiple of TILE)
+  int64_t s_cap;     // points the two arrays above hold
+  uint4* Xp;         // workspace: packed copy of X
+  int64_t xp_bytes;
   int profiling;
   hipEvent_t ev[4];
   int ev_valid;
@@ -619,26 +660,47 @@ int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int6
   return EJOIN_OK;
 }
 
-int ensure_workspace(ejoin_ctx* ctx, int64_t n) {
-  if (n <= ctx->s_cap) return EJOIN_OK;
-  if (ctx->s || ctx->H) {
-    EJ_TRY(hipDeviceSynchronize());
-    if (ctx->s) EJ_TRY(hipFree(ctx->s));
-    ctx->s = nullptr;
-    if (ctx->H) EJ_TRY(hipFree(ctx->H));
-    ctx->H = nullptr;
-    ctx->s_cap = 0;
+int64_t pad_rows(int64_t n) { return (n + TILE - 1) / TILE * TILE; }
+int64_t pad_dims(int32_t d) { return ((int64_t)d + KPAD - 1) / KPAD * KPAD; }
+
+// d = 0: only the per-point arrays (norms, augmentation rows); d > 0: also the packed copy of X.
+int ensure_workspace(ejoin_ctx* ctx, int64_t n, int32_t d) {
+  if (n > ctx->s_cap) {
+    if (ctx->s || ctx->H) {
+      EJ_TRY(hipDeviceSynchronize());
+      if (ctx->s) EJ_TRY(hipFree(ctx->s));
+      ctx->s = nullptr;
+      if (ctx->H) EJ_TRY(hipFree(ctx->H));
+      ctx->H = nullptr;
+      ctx->s_cap = 0;
+    }
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->s), (size_t)n * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->H), (size_t)pad_rows(n) * sizeof(uint4));
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (ctx->s) (void)hipFree(ctx->s);
+      ctx->s = nullptr;
+      if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
+      return fail_hip(ctx, e, "hipMalloc(workspace)");
+    }
+    ctx->s_cap = n;
   }
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->s), (size_t)n * sizeof(float));
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->H), (size_t)((n + TILE - 1) / TILE * TILE) * sizeof(uint4));
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    if (ctx->s) (void)hipFree(ctx->s);
-    ctx->s = nullptr;
-    if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
-    return fail_hip(ctx, e, "hipMalloc(workspace)");
+  const int64_t need = d > 0 ? pad_rows(n) * pad_dims(d) * 2 : 0;
+  if (need > ctx->xp_bytes) {
+    if (ctx->Xp) {
+      EJ_TRY(hipDeviceSynchronize());
+      EJ_TRY(hipFree(ctx->Xp));
+      ctx->Xp = nullptr;
+      ctx->xp_bytes = 0;
+    }
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->Xp), (size_t)need);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
+      return fail_hip(ctx, e, "hipMalloc(packed X)");
+    }
+    ctx->xp_bytes = need;
   }
-  ctx->s_cap = n;
   return EJOIN_OK;
 }
 
@@ -680,15 +742,15 @@ struct DeviceGuard {
 template <bool COUNT>
 int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs, float* dist2,
              uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint64_t* total, hipStream_t st) {
-  int rc = ensure_workspace(ctx, n);
+  int rc = ensure_workspace(ctx, n, d);
   if (rc != EJOIN_OK) return rc;
   JoinArgs a;
   memset(&a, 0, sizeof(a));
-  a.X = X;
+  a.Xp = ctx->Xp;
+  a.npad = pad_rows(n);
   a.H = ctx->H;
   a.status = ctx->status;
   a.n = n;
-  a.ld = ld;
   a.nslices = (d + KPAD - 1) / KPAD * (KPAD / KSLICE);
   a.thr = -0.5f * (eps * eps);
   a.ntiles = (uint32_t)((n + TILE - 1) / TILE);
@@ -703,6 +765,12 @@ int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld
   if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
   rc = launch_prepare(ctx, X, n, d, ld, COUNT ? a.total : a.n_pairs, st);
   if (rc != EJOIN_OK) return rc;
+  {
+    const int nkb = a.nslices;
+    const int64_t chunks = (int64_t)nkb * a.npad * 4;
+    hipLaunchKernelGGL(k_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X, n, a.npad, ld, nkb, ctx->Xp);
+    EJ_TRY(hipGetLastError());
+  }
   if (COUNT) {
     hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counts, n, 0u);
     EJ_TRY(hipGetLastError());
@@ -768,17 +836,18 @@ int ejoin_destroy(ejoin_ctx* ctx) {
   if (ctx->status) (void)hipFree(ctx->status);
   if (ctx->s) (void)hipFree(ctx->s);
   if (ctx->H) (void)hipFree(ctx->H);
+  if (ctx->Xp) (void)hipFree(ctx->Xp);
   for (int i = 0; i < 4; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
   delete ctx;
   return EJOIN_OK;
 }
 
-int ejoin_reserve(ejoin_ctx* ctx, int64_t n) {
-  if (!ctx || n < 1) return EJOIN_EINVAL;
+int ejoin_reserve(ejoin_ctx* ctx, int64_t n, int32_t d) {
+  if (!ctx || n < 1 || d < 1 || d > 65536) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return ensure_workspace(ctx, n);
+  return ensure_workspace(ctx, n, d);
 }
 
 const char* ejoin_strerror(int code) {
@@ -787,7 +856,7 @@ const char* ejoin_strerror(int code) {
     case EJOIN_EINVAL: return "invalid argument (null pointer, size out of range, ld not a multiple of 64 or < roundup(d,64), X not 128-byte aligned)";
     case EJOIN_EUNSUPPORTED: return "unsupported device (gfx950 required) or problem size";
     case EJOIN_EHIP: return "HIP runtime error (see ejoin_last_hip_error)";
-    case EJOIN_ENOMEM: return "out of device memory for the workspace (20 bytes per point)";
+    case EJOIN_ENOMEM: return "out of device memory for the workspace (20 bytes per point plus a packed copy of X)";
     default: return "unknown error code";
   }
 }
@@ -831,7 +900,7 @@ int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   if (rows > 32 * 65535 || cols > 32 * 65535) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  rc = ensure_workspace(ctx, n);
+  rc = ensure_workspace(ctx, n, 0);
   if (rc != EJOIN_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   rc = launch_prepare(ctx, X, n, d, ld, nullptr, st);
