@@ -11,6 +11,7 @@
 #include <string.h>
 #include <math.h>
 #include <new>
+#include <type_traits>
 
 #include "ejoin.h"
 
@@ -29,16 +30,14 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 constexpr int TILE = 256;     // a workgroup computes a TILE x TILE block of the distance matrix
 constexpr int KPAD = 64;      // d is processed rounded up to a multiple of KPAD (zero padded by the caller)
 constexpr int KSLICE = 32;    // coordinates per LDS stage (64 B per row)
-constexpr int NSTAGE = 4;     // ring of LDS stages; up to NSTAGE-1 slices are in flight from L2/HBM
+constexpr int NSTAGE = 4;     // ring of LDS stages; NSTAGE-1 slices are in flight from L2/HBM
+constexpr int DIST = NSTAGE - 1;
 constexpr int THREADS = 512;  // 8 wavefronts: 2 (rows) x 4 (columns), wave tile 128 x 64
 constexpr int SB = 16;        // tiles per super-block edge (one super-block = 256 tiles = one pass of the chip)
 constexpr int PANEL_BYTES = TILE * KSLICE * 2;  // 16 KB : one operand panel of one stage
 constexpr int STAGE_BYTES = 2 * PANEL_BYTES;    // A panel + B panel
-constexpr int AUX_OFF = NSTAGE * STAGE_BYTES;   // [tile parity][A rows | B rows][TILE] x 16 B augmentation rows
-constexpr int AUX_BYTES = 2 * 2 * TILE * 16;
-constexpr int ZERO_OFF = AUX_OFF + AUX_BYTES;   // 2 KB of zeros
-constexpr int ZERO_BYTES = 2048;
-constexpr int STG_OFF = ZERO_OFF + ZERO_BYTES;          // per-wave result staging: STG_CAP entries of (i, j, d2)
+constexpr int DUMP_OFF = NSTAGE * STAGE_BYTES;  // 1 KB that absorbs the copies issued past the end of the work
+constexpr int STG_OFF = DUMP_OFF + 1024;        // per-wave result staging: STG_CAP entries of (i, j, d2)
 constexpr int STG_CAP = 128;
 constexpr int STG_WAVE_BYTES = STG_CAP * 12;
 constexpr int LDS_BYTES = STG_OFF + 8 * STG_WAVE_BYTES;
@@ -53,15 +52,14 @@ constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
 // ds_read_b128 serves 16 lanes per clock; 16 consecutive rows at the same logical chunk then fall
 // into 16 distinct 16-byte bank groups (4 rows per 256 B bank line x 4 positions).  This is the
 // role the XOR swizzle of Section 3.3.5 (Eq. 2) plays on the A100's 32 banks.
-__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+__host__ __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
 struct JoinArgs {
-  const uint4* Xp;         // packed copy of X, see k_pack
+  const uint4* Xp;         // packed copy of X plus the augmentation block, see k_pack / k_aux
   int64_t npad;            // rows of Xp per k-block: n rounded up to a multiple of TILE
-  const uint4* H;          // per point: the 16-byte augmentation row, see k_aux
   const uint32_t* status;  // device status word
   int64_t n;
-  int nslices;  // roundup(d, 64) / 32
+  int nslices;  // roundup(d, 64) / 32 : k-blocks of X (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntiles;  // ceil(n / TILE)
   uint32_t nsb;     // ceil(ntiles / SB)
@@ -139,7 +137,8 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
 }
 
 // Rows past the end of the data set use this augmentation row: -60000 in place of -s/2, so that
-// none of their pairs can pass the filter (and nothing non-finite enters the matrix cores).
+// none of their pairs passes the filter for any ordinary epsilon (the rare path masks them exactly)
+// and nothing non-finite enters the matrix cores.
 __device__ __forceinline__ uint4 aux_row_out_of_range() { return make_uint4(0xFB53u /* -60000 in FP16 */, 0u, 0x3C003C00u, 0x3C00u); }
 
 // Augmentation rows.  Step 3 of Section 3.1 (dist^2 = s_i + s_j - 2 a_ij) is folded into the
@@ -151,8 +150,12 @@ __device__ __forceinline__ uint4 aux_row_out_of_range() { return make_uint4(0xFB
 // step a row is used as is (k = 0..7; k = 8..15 are zero), as the B operand its two halves are
 // swapped, { c, c, c, 0, q1, q2, q3, 0 }, so that  A_i . B_j = c (p1+p2+p3)_i + c (q1+q2+q3)_j
 // = -s_i/2 - s_j/2  (every product is exact in FP32).
-// Rows n .. npad-1 (npad = n rounded up to a multiple of the tile edge) get the out-of-range row.
-__global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max, uint4* __restrict__ H) {
+// H (npad rows) serves the dense-tile kernel.  For the join the rows are also written as one more
+// k-block behind the packed X (`aug`, may be null): row r = { chunk 0: H_r, chunk 1: H_r with halves
+// swapped, chunks 2 and 3: zero }, chunk c at position c ^ swz(r) like every other block, so that the
+// join kernel streams the augmentation step through the same LDS stages as the data.
+__global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max,
+                      uint4* __restrict__ H, uint4* __restrict__ aug) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t mb = status_and_max[1];
   int m = 0;
@@ -165,12 +168,9 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
   }
   if (i == 0) status_and_max[0] = st;
   if (i >= npad) return;
-  if (i >= n) {
-    H[i] = aux_row_out_of_range();
-    return;
-  }
   uint4 h = make_uint4(0, 0, 0, 0);
-  if (st == ST_OK) {
+  if (i >= n) h = aux_row_out_of_range();
+  else if (st == ST_OK) {
     const float v = ldexpf(-0.5f * s[i], -m);
     const _Float16 p1 = (_Float16)v;
     const float r1 = v - (float)p1;
@@ -184,6 +184,14 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
     h.w = bits(c);
   }
   H[i] = h;
+  if (aug) {
+    const int sw = swz((int)(i & 255));
+    uint4* row = aug + i * 4;
+    row[0 ^ sw] = h;
+    row[1 ^ sw] = make_uint4(h.z, h.w, h.x, h.y);
+    row[2 ^ sw] = make_uint4(0, 0, 0, 0);
+    row[3 ^ sw] = make_uint4(0, 0, 0, 0);
+  }
 }
 
 __device__ __forceinline__ half8 as_half8(uint4 v) { return __builtin_bit_cast(half8, v); }
@@ -290,15 +298,6 @@ struct TileCursor {
   }
 };
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else if constexpr (N == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else static_assert(N == 0, "unsupported count");
-}
-
 // Workgroup barrier without the fences of __syncthreads(): those make the compiler wait for every
 // outstanding global->LDS copy (vmcnt(0)) at each barrier, which would serialise the copy pipeline.
 // The kernel orders its LDS traffic itself: copies are certified with counted vmcnt waits before the
@@ -306,36 +305,19 @@ __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // One global->LDS copy instruction: every lane moves 16 bytes from sbase + voff (sbase uniform) to
-// LDS address lds_addr + 16 * lane (lds_addr uniform, goes through M0).  Written as inline assembly
-// on purpose: for the builtin form the compiler assumes the instruction may also count on lgkmcnt,
-// and from then on turns every LDS wait into lgkmcnt(0), which breaks the overlap of fragment reads
-// with MFMAs.  The copies are tracked by hand with counted vmcnt waits (wait_vmcnt).
+// LDS address lds_addr + LDS_IMM + 16 * lane (lds_addr uniform, goes through M0).  Written as inline
+// assembly on purpose: for the builtin form the compiler assumes the instruction may also count on
+// lgkmcnt, and from then on turns every LDS wait into lgkmcnt(0), which breaks the overlap of
+// fragment reads with MFMAs.  The copies are tracked by hand with counted vmcnt waits.
+template <int LDS_IMM>
 __device__ __forceinline__ void copy16_to_lds(uint32_t lds_addr, const void* sbase, uint32_t voff) {
   asm volatile(
-      "s_mov_b32 m0, %0\n\t"
+      "s_add_u32 m0, %0, %3\n\t"
       "s_nop 0\n\t"
       "global_load_lds_dwordx4 %1, %2"
       :
-      : "s"(lds_addr), "v"(voff), "s"(sbase)
-      : "memory", "m0");
-}
-
-// The augmentation rows of a wave tile: four A-side rows (32 rows = 512 B apart) and two B-side rows,
-// read with LDS instructions the compiler does not see as LDS accesses (it would otherwise wait for
-// all outstanding global->LDS copies first).  The wait is part of the same statement, so every use
-// of the results is ordered after it.
-__device__ __forceinline__ void lds_read_aux(uint32_t addr_a, uint32_t addr_b, uint4 (&ra)[4], uint4 (&rb)[2]) {
-  asm volatile(
-      "ds_read_b128 %0, %6\n\t"
-      "ds_read_b128 %1, %6 offset:512\n\t"
-      "ds_read_b128 %2, %6 offset:1024\n\t"
-      "ds_read_b128 %3, %6 offset:1536\n\t"
-      "ds_read_b128 %4, %7\n\t"
-      "ds_read_b128 %5, %7 offset:512\n\t"
-      "s_waitcnt lgkmcnt(0)"
-      : "=&v"(ra[0]), "=&v"(ra[1]), "=&v"(ra[2]), "=&v"(ra[3]), "=&v"(rb[0]), "=&v"(rb[1])
-      : "v"(addr_a), "v"(addr_b)
-      : "memory");
+      : "s"(lds_addr), "v"(voff), "s"(sbase), "n"(LDS_IMM)
+      : "memory", "m0", "scc");
 }
 
 template <bool COUNT>
@@ -346,61 +328,52 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int r32 = lane & 31, hi = lane >> 5;
-  const int nsl = a.nslices;
-  const int DIST = nsl < NSTAGE - 1 ? nsl : NSTAGE - 1;  // slices kept in flight
-
-  reinterpret_cast<uint32_t*>(lds + ZERO_OFF)[tid] = 0;
-  static_assert(ZERO_BYTES == THREADS * 4, "one dword per thread");
+  const int nsl = a.nslices;       // data slices per tile
+  const int nslT = nsl + 1;        // plus the augmentation slice (nslT >= 3)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
   // --- global->LDS copies.  One global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 B) = 16 rows of a
   // panel; in the packed layout that is 1 KB of contiguous global memory.  Wave w copies blocks w and
-  // w + 8 of both 16 KB panels of a slice.  pa / pb: the panels' global addresses (uniform).
+  // w + 8 of both 16 KB panels of a slice: 4 copy instructions per wave and slice, always (past the
+  // end of the work they are pointed at a dump area), so the number of outstanding copies is a constant.
   const char* Xb = reinterpret_cast<const char*>(a.Xp);
   const int64_t kstride = a.npad * 64;  // bytes from one k-block of Xp to the next
-  const uint32_t lane16 = lane * 16;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-  auto issue_slice = [&](const char* pa, const char* pb, uint32_t stage) {
-    const uint32_t base = lds0 + stage * STAGE_BYTES;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const uint32_t blk = (wave + 8 * q) * 1024;
-      copy16_to_lds(base + blk, pa + blk, lane16);
-      copy16_to_lds(base + PANEL_BYTES + blk, pb + blk, lane16);
-    }
-  };
-  // augmentation rows of the tile's 256 rows and 256 columns: 8 KB, copied with one more instruction
-  // per wave (waves 0..3: rows I*256 + 64*wave .. +63; waves 4..7: the columns); H is padded to a
-  // multiple of the tile edge, so no clamping is needed
-  auto aux_buf = [&](uint32_t parity) -> uint4* { return reinterpret_cast<uint4*>(lds + AUX_OFF) + parity * (2 * TILE); };
-  auto issue_aux = [&](uint32_t I, uint32_t J, uint32_t parity) {
-    const int64_t g0 = (int64_t)(wave < 4 ? I : J) * TILE + (wave & 3) * 64;
-    copy16_to_lds(lds0 + AUX_OFF + parity * (2 * TILE * 16) + wave * 1024, a.H + g0, lane16);
+  const uint32_t voff0 = lane * 16 + wave * 1024, voff1 = voff0 + 8192;
+  auto issue_slice = [&](const char* pa, const char* pb, uint32_t lds_stage /* LDS address of the stage + wave*1024 */) {
+    copy16_to_lds<0>(lds_stage, pa, voff0);
+    copy16_to_lds<8192>(lds_stage, pa, voff1);
+    copy16_to_lds<PANEL_BYTES>(lds_stage, pb, voff0);
+    copy16_to_lds<PANEL_BYTES + 8192>(lds_stage, pb, voff1);
   };
 
   // --- fragment read addressing (byte offsets inside a stage).  A operand of
   // v_mfma_f32_32x32x16_f16: lane l supplies row l%32, coordinates 8*(l/32) .. +7 of the 16-wide step.
   // m-tile / n-tile t adds 32 rows = 2048 B (swz unchanged: 32 rows = 8 groups of 4).
-  int offA[2], offB[2];
+  // In the augmentation slice the A operand reads chunk 0 (lanes 32..63: chunk 2 = zeros) and the
+  // B operand chunk 1 (chunk 3).
+  uint32_t offA[2], offB[2], offB_aug;
   {
     const int rowA = wm * 128 + r32, rowB = wn * 64 + r32;
 #pragma unroll
     for (int k16 = 0; k16 < 2; ++k16) {
-      offA[k16] = rowA * 64 + (((2 * k16 + hi) ^ swz(rowA)) << 4);
-      offB[k16] = PANEL_BYTES + rowB * 64 + (((2 * k16 + hi) ^ swz(rowB)) << 4);
+      offA[k16] = lds0 + rowA * 64 + (((2 * k16 + hi) ^ swz(rowA)) << 4);
+      offB[k16] = lds0 + PANEL_BYTES + rowB * 64 + (((2 * k16 + hi) ^ swz(rowB)) << 4);
     }
+    offB_aug = lds0 + PANEL_BYTES + rowB * 64 + (((1 + 2 * hi) ^ swz(rowB)) << 4);
   }
-  auto load_frags = [&](uint32_t stage, int k16, half8 (&fa)[4], half8 (&fb)[2]) {
-    const char* st = lds + stage * STAGE_BYTES;
+  const uint32_t offA_aug = lds0 + (wm * 128 + r32) * 64 + (((2 * hi) ^ swz(wm * 128 + r32)) << 4);
+  auto load_frags = [&](uint32_t stage_off, uint32_t oa, uint32_t ob, half8 (&fa)[4], half8 (&fb)[2]) {
+    const __attribute__((address_space(3))) char* pa = (const __attribute__((address_space(3))) char*)(uintptr_t)(oa + stage_off);
+    const __attribute__((address_space(3))) char* pb = (const __attribute__((address_space(3))) char*)(uintptr_t)(ob + stage_off);
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const half8*>(st + offA[k16] + mt * 2048);
+    for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const __attribute__((address_space(3))) half8*>(pa + mt * 2048);
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) fb[nt] = *reinterpret_cast<const half8*>(st + offB[k16] + nt * 2048);
+    for (int nt = 0; nt < 2; ++nt) fb[nt] = *reinterpret_cast<const __attribute__((address_space(3))) half8*>(pb + nt * 2048);
   };
 
   float16v acc[4][2];
-  // One 16-wide step: the eight MFMAs of the wave tile on fragments (fa, fb), while the fragments of
-  // the following step (na, nb) are read from LDS.  The scheduling hints spread the six LDS reads
-  // between the first MFMAs, so that they complete under the remaining ones.
+  // One 16-wide step: the eight MFMAs of the wave tile.  The scheduling hints spread the LDS reads of
+  // the following step's fragments between the first MFMAs, so that they complete under the rest.
   auto mma_only = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
@@ -419,11 +392,12 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   auto interleave_hint = [&]() {
 #pragma unroll
     for (int i = 0; i < 6; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
   };
+
   // --- per-wave result staging (pair mode): entries are appended in LDS and written out in bulk
   // with one atomic per flush (wavefront ballot + prefix ranks + one atomic per wavefront flush).
   uint32_t* stg = reinterpret_cast<uint32_t*>(lds + STG_OFF + wave * STG_WAVE_BYTES);
@@ -455,83 +429,81 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   bool have = tc.next(I, J);
   if (!have) return;
   bool have_next = tc.next(In, Jn);
-  uint32_t T = 0;   // tiles done by this workgroup
-  uint32_t G = 0;   // slices computed so far (stage = G % NSTAGE)
-  uint32_t Gi = 0;  // slices issued so far
-  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` of the current tile,
-  // or, once that tile is fully issued, of the next one.  The first slice of a tile carries the
-  // tile's augmentation rows as a fifth copy instruction, issued first.
+  uint32_t G = 0;  // slices computed so far (stage = G % NSTAGE); slices issued so far = G + DIST
+  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` (0 .. nslT-1) of the
+  // current tile or, once that is fully issued, of the next one; after the last tile it keeps
+  // issuing copies of valid memory into the dump area.
   int iks = 0;
-  bool issue_on_next = false;
-  bool issue_valid = true;
-  bool young5 = false;  // the most recently issued slice had 5 copies
+  bool issue_live = true;       // the issue cursor still points at real work
+  bool issue_on_next = false;   // ... of the tile after the one being computed
   const char* pa = Xb + (int64_t)I * (TILE * 64);
   const char* pb = Xb + (int64_t)J * (TILE * 64);
-  auto issue_one = [&]() {
-    if (!issue_valid) return;
-    young5 = (iks == 0);
-    if (iks == 0) {
-      if (issue_on_next) issue_aux(In, Jn, (T + 1) & 1); else issue_aux(I, J, T & 1);
+  const uint32_t lds_w = lds0 + wave * 1024;
+  auto issue_one = [&](uint32_t Gissue) {
+    if (issue_live) {
+      issue_slice(pa, pb, lds_w + (Gissue % NSTAGE) * STAGE_BYTES);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, Xb, lane * 16);
     }
-    issue_slice(pa, pb, Gi % NSTAGE);
-    ++Gi;
     pa += kstride;
     pb += kstride;
-    if (++iks == nsl) {
+    if (++iks == nslT) {
       iks = 0;
-      if (!issue_on_next && have_next) {
-        issue_on_next = true;
-        pa = Xb + (int64_t)In * (TILE * 64);
-        pb = Xb + (int64_t)Jn * (TILE * 64);
-      } else {
-        issue_valid = false;
-      }
+      const bool to_next = issue_live && !issue_on_next && have_next;
+      issue_live = to_next;
+      issue_on_next = to_next;
+      pa = Xb + (int64_t)(to_next ? In : 0) * (TILE * 64);
+      pb = Xb + (int64_t)(to_next ? Jn : 0) * (TILE * 64);
     }
   };
-  for (int q = 0; q < DIST; ++q) issue_one();
-  // slice 0 (and the augmentation rows) have landed when only the DIST-1 younger slices' copies
-  // (4 per slice and wave) are outstanding
-  if (DIST == 3) wait_vmcnt<8>(); else if (DIST == 2) wait_vmcnt<4>(); else wait_vmcnt<0>();
+  for (int q = 0; q < DIST; ++q) issue_one(q);
+  // slice 0 has landed when only the copies of the DIST-1 younger slices (4 per slice and wave) are outstanding
+  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   __syncthreads();
   half8 fa0[4], fb0[2], fa1[4], fb1[2];
-  load_frags(0, 0, fa0, fb0);
+  load_frags(0, offA[0], offB[0], fa0, fb0);
+
+  // One data slice (G-th of the stream).  FIRST: first slice of a tile (accumulators start from zero);
+  // LAST: last data slice of a tile (the fragments read ahead are those of the augmentation slice).
+  auto data_slice = [&](auto first_c, auto last_c) {
+    constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+    const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
+    // (a) this wave's copies of slice G+1 have landed once only slice G+2's four are outstanding
+    if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
+    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
+    wg_barrier();
+    // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
+    //     (the second one reads from slice G+1, which barrier (b) has certified)
+    load_frags(st_cur, offA[1], offB[1], fa1, fb1);
+    if constexpr (FIRST) mma_first(fa0, fb0); else mma_only(fa0, fb0);
+    interleave_hint();
+    // (c) refill the stage slice G-1 occupied with slice G+DIST
+    issue_one(G + DIST);
+    load_frags(st_nxt, LAST ? offA_aug : offA[0], LAST ? offB_aug : offB[0], fa0, fb0);
+    mma_only(fa1, fb1);
+    interleave_hint();
+    ++G;
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
 
   while (have) {
-    for (int ks = 0; ks < nsl; ++ks, ++G) {
-      // (a) this wave's copies of slice G+1 have landed once only the younger slice's copies are outstanding
-      {
-        const bool younger = Gi > G + 2;  // at most one younger slice (DIST <= 3)
-        if (dirty || !younger) { wait_vmcnt<0>(); dirty = false; }
-        else if (young5) wait_vmcnt<5>();
-        else wait_vmcnt<4>();
-      }
-      // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
-      wg_barrier();
-      // (c) refill the stage slice G-1 occupied
-      if (Gi < G + 1 + DIST) issue_one();
-      // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
-      //     (the second one reads from slice G+1, which barrier (b) has certified)
-      load_frags(G % NSTAGE, 1, fa1, fb1);
-      if (ks == 0) mma_first(fa0, fb0); else mma_only(fa0, fb0);
-      interleave_hint();
-      load_frags((G + 1) % NSTAGE, 0, fa0, fb0);
-      mma_only(fa1, fb1);
-      interleave_hint();
-    }
-
-    // ---------------- epilogue: the augmentation step, then the filter
+    // ---------------- the nsl >= 2 data slices of the tile
+    data_slice(T_{}, F_{});
+    for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{});
+    data_slice(F_{}, T_{});
+    // ---------------- the augmentation slice: one step, then the filter
     {
-      // lanes 32..63 supply coordinates 8..15 of the step, which are zero
-      const uint32_t ab = (uint32_t)(uintptr_t)aux_buf(T & 1);
-      const uint32_t zero = (uint32_t)(uintptr_t)(lds + ZERO_OFF);
-      uint4 ra[4], rb[2];
-      lds_read_aux(hi ? zero : ab + (wm * 128 + r32) * 16, hi ? zero : ab + (TILE + wn * 64 + r32) * 16, ra, rb);
-      half8 ha[4], hb[2];
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt) ha[mt] = as_half8(ra[mt]);
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) hb[nt] = as_half8(make_uint4(rb[nt].z, rb[nt].w, rb[nt].x, rb[nt].y));
-      mma_only(ha, hb);
+      if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
+      else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      wg_barrier();
+      mma_only(fa0, fb0);
+      issue_one(G + DIST);
+      ++G;
+    }
+    {
       // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of tile (mt, nt) in lane l is the pair
       //   i = I*256 + wm*128 + mt*32 + 8*(r/4) + 4*(l/32) + r%4 ,  j = J*256 + wn*64 + nt*32 + l%32.
       const bool diag = (I == J);
@@ -603,6 +575,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         }
       }
     }
+    // first fragments of the next tile (slice G was certified by the augmentation slice's barrier);
+    // read after the filter to keep its registers free
+    load_frags((G % NSTAGE) * STAGE_BYTES, offA[0], offB[0], fa0, fb0);
     I = In;
     J = Jn;
     have = have_next;
@@ -610,8 +585,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       have_next = tc.next(In, Jn);
       issue_on_next = false;  // the issue cursor, if it had moved on, is now on the current tile
     }
-    ++T;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the dump copies must land before the wave ends
   if (!COUNT) flush();
   if (COUNT && hits && lane == 0) atomicAdd(a.total, hits);
 }
@@ -685,7 +660,7 @@ int ensure_workspace(ejoin_ctx* ctx, int64_t n, int32_t d) {
     }
     ctx->s_cap = n;
   }
-  const int64_t need = d > 0 ? pad_rows(n) * pad_dims(d) * 2 : 0;
+  const int64_t need = d > 0 ? pad_rows(n) * (pad_dims(d) + KSLICE) * 2 : 0;  // data k-blocks + the augmentation block
   if (need > ctx->xp_bytes) {
     if (ctx->Xp) {
       EJ_TRY(hipDeviceSynchronize());
@@ -715,13 +690,15 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
 }
 
 // Steps shared by the join and the dense-tile call: reset, norms (+ max), augmentation rows.
-int launch_prepare(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, unsigned long long* counter, hipStream_t st) {
+// aug: where the join wants the augmentation k-block (null for the dense-tile call).
+int launch_prepare(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, unsigned long long* counter, uint4* aug,
+                   hipStream_t st) {
   hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctx->status, counter);
   EJ_TRY(hipGetLastError());
   int rc = launch_norms(ctx, X, n, d, ld, ctx->s, ctx->status + 1, st);
   if (rc != EJOIN_OK) return rc;
-  const int64_t npad = (n + TILE - 1) / TILE * TILE;
-  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, ctx->s, n, npad, ctx->status, ctx->H);
+  const int64_t npad = pad_rows(n);
+  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, ctx->s, n, npad, ctx->status, ctx->H, aug);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -748,7 +725,6 @@ int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld
   memset(&a, 0, sizeof(a));
   a.Xp = ctx->Xp;
   a.npad = pad_rows(n);
-  a.H = ctx->H;
   a.status = ctx->status;
   a.n = n;
   a.nslices = (d + KPAD - 1) / KPAD * (KPAD / KSLICE);
@@ -763,7 +739,7 @@ int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld
   a.total = reinterpret_cast<unsigned long long*>(total);
 
   if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
-  rc = launch_prepare(ctx, X, n, d, ld, COUNT ? a.total : a.n_pairs, st);
+  rc = launch_prepare(ctx, X, n, d, ld, COUNT ? a.total : a.n_pairs, ctx->Xp + (int64_t)a.nslices * a.npad * 4, st);
   if (rc != EJOIN_OK) return rc;
   {
     const int nkb = a.nslices;
@@ -903,7 +879,7 @@ int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   rc = ensure_workspace(ctx, n, 0);
   if (rc != EJOIN_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  rc = launch_prepare(ctx, X, n, d, ld, nullptr, st);
+  rc = launch_prepare(ctx, X, n, d, ld, nullptr, nullptr, st);
   if (rc != EJOIN_OK) return rc;
   hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->H, ctx->status, n, ld, k16_steps(d), i0, j0, rows, cols, out);
   EJ_TRY(hipGetLastError());
