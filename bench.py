@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 
 PEAK_FP16_TFLOPS = 2500.0  # MI355X dense FP16 MFMA, published
 
+# Bytes k_join fetches into L2 from the memory side plus bytes it writes, per launch, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy of known size
+# (profiles/k_join_workload3_hbm_counters.txt).  Only measured for the default workload.
+MEASURED_TRAFFIC_BYTES = {(3, 16, "pairs"): 1.992e12}
+
 
 def load_eps(workload: int, S: int) -> float:
     with open(os.path.join(ROOT, "paper_2508_21230_amd", "workloads_eps.json")) as f:
@@ -122,7 +127,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16 inputs, f32 accumulate",
+        "dtype": "f16",
+        "accumulate": "f32",
         "data": "synthetic",
         "config": {"workload": f"configs[{w - 1}]: n={n}, d={d}, {spec['kind']}, S={S}, eps={eps:.7g}, mode={args.mode}",
                    "n": n, "d": d, "selectivity_target": S, "eps": eps, "mode": args.mode},
@@ -131,7 +137,7 @@ def main():
         "achieved_selectivity": (2.0 * (found - n) / n) if args.mode == "pairs" else 2.0 * found / n,
         "kernel_ms": {"norms": sum(norm_ms) / len(norm_ms), "join": jm, "join_min": min(join_ms)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS,
-                     "traffic": None, "kernel": "k_join", "flop_per_launch": flop_exec, "tiles": tiles},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w, S, args.mode)) if args.n is None else None, "kernel": "k_join", "flop_per_launch": flop_exec, "tiles": tiles},
     }
     if not args.no_cpu_baseline:
         rows = args.cpu_rows or max(8, int(2.0e12 / (n * d * 16)))  # ~10-30 s of host work
