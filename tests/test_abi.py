@@ -1,0 +1,47 @@
+"""The C-ABI library loads without a GPU and exports every function include/ejoin.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ejoin.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ejoin_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2508_21230_amd as pkg
+    lib = pkg.load_library()
+    names = declared_functions()
+    assert len(names) >= 12 and "ejoin_selfjoin_pairs" in names and "ejoin_selfjoin_count" in names
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in include/ejoin.h but not exported"
+
+
+def test_host_only_entry_points():
+    import paper_2508_21230_amd as pkg
+    lib = pkg.load_library()
+    assert lib.ejoin_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(lib.ejoin_strerror(code)) > 0
+    # upper-triangular 256 x 256 tiles, diagonal included
+    assert pkg.tiles_evaluated(1) == 1 and pkg.tiles_evaluated(256) == 1 and pkg.tiles_evaluated(257) == 3
+    assert pkg.tiles_evaluated(1_000_000) == 3907 * 3908 // 2
+    assert pkg.tiles_evaluated(0) == 0
+    # argument checks that need no device
+    assert lib.ejoin_create(None, 0) == -1
+    assert lib.ejoin_destroy(None) == -1
+    assert lib.ejoin_set_profiling(None, 1) == -1
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    import pytest
+    import torch
+    import paper_2508_21230_amd as pkg
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    with pytest.raises(pkg.EJoinError):
+        pkg.EJoin(0)
