@@ -539,9 +539,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
       else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
       wg_barrier();
-      mma_only(fa0, fb0);
       issue_one(G + DIST);
       ++G;
+      mma_only(fa0, fb0);
     }
     {
       // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of tile (mt, nt) in lane l is the pair
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       const bool skip = diag && (wm * 128 >= wn * 64 + 64);
       // cheap filter: which of the eight 32 x 32 blocks of this wave tile hold a passing pair at all
       uint32_t blocks_hit = 0;
-      if (!skip) {
+      {
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
@@ -564,7 +564,16 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
             if (__ballot(m >= a.thr)) blocks_hit |= 1u << (mt * 2 + nt);
           }
         }
+        // the filter of a block only needs that block's last MFMA: let the VALU work of block b run
+        // under the augmentation MFMAs of the blocks after it
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) {
+          __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
       }
+      if (skip) blocks_hit = 0;
       // rare path, one block at a time
       while (blocks_hit) {
         const int b = __builtin_ctz(blocks_hit);

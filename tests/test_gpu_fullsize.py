@@ -45,7 +45,7 @@ def gpu_pair_properties(pairs_t, found, n):
     return i, j
 
 
-@pytest.mark.parametrize("w,S,rows", [(2, 64, 256), (3, 16, 48), (4, 16, 64), (4, 128, 64), (5, 64, 96)])
+@pytest.mark.parametrize("w,S,rows", [(2, 64, 256), (3, 16, 48), (4, 16, 64), (4, 128, 64), (4, 1024, 16), (5, 64, 96)])
 def test_full_size_pairs_against_oracle_rows(ej, w, S, rows):
     spec = datagen.WORKLOADS[w]
     n, d = spec["n"], spec["d"]

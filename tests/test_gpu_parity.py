@@ -208,3 +208,64 @@ def test_invalid_arguments_are_rejected(ej):
     Z = torch.zeros(10 * 128 + 8, dtype=torch.float16, device="cuda")[8:].view(10, 128)
     with pytest.raises(pkg.EJoinError):
         ej.norms(Z)                                      # base not 128-byte aligned
+
+
+# ------------------------------------------------------------------ data range
+def test_large_norms_use_the_scaled_split(ej):
+    # Sift-like data: integer coordinates 0..218 in d = 128 (the paper's Sift10M has epsilon ~ 122-152,
+    # data-set table); norms ~ 1e6 exceed the FP16 range of -s/2, so the augmentation rows are scaled.
+    rng = np.random.default_rng(11)
+    n, d = 1500, 128
+    centres = rng.integers(0, 219, size=(12, d))
+    X = np.clip(centres[rng.integers(0, 12, size=n)] + rng.normal(0, 8, size=(n, d)).round(), 0, 218).astype(np.float16).view(np.uint16)
+    P = orc.decode(X)
+    assert orc.norms(P).max() > 3e5
+    eps = orc.select_eps_all_pairs(P, 30)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    pairs, d2, found = run_pairs(ej, dev(X), eps, capacity=ora_pairs.shape[0] + 4096)
+    assert ej.status() == 0
+    st = parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+    print("  ", st, flush=True)
+    dense = ej.dist2_tile(dev(X), 0, 0, n, n).cpu().numpy()
+    assert np.array_equal(dense[pairs[:, 0], pairs[:, 1]], d2) and np.all(np.diag(dense) == 0.0)
+
+
+def test_status_reports_out_of_range_and_non_finite_input(ej):
+    n, d = 600, 64
+    X = datagen.generate(1, n=n)[:, :d].copy()
+    Xd = dev(X)
+    # fine
+    _, _, npairs = ej.selfjoin_pairs(Xd, 1.0, 1000)
+    assert ej.status() == 0
+    # norms >= 2^31: 64 coordinates of 60000 -> s = 2.3e11
+    big = np.full((n, d), np.float16(60000.0)).view(np.uint16)
+    p, d2, npairs = ej.selfjoin_pairs(dev(big), 1.0, 1000)
+    assert ej.status() == 1 and int(npairs.cpu()[0]) == 0
+    counts, total = ej.selfjoin_count(dev(big), 1.0)
+    assert ej.status() == 1 and int(total.cpu()[0]) == 0 and int(counts.cpu().abs().sum()) == 0
+    # Inf in the input
+    bad = X.copy()
+    bad[17, 3] = 0x7C00
+    p, d2, npairs = ej.selfjoin_pairs(dev(bad), 1.0, 1000)
+    assert ej.status() == 2 and int(npairs.cpu()[0]) == 0
+    # and the context recovers
+    _, _, npairs = ej.selfjoin_pairs(Xd, 1.0, 1000)
+    assert ej.status() == 0 and int(npairs.cpu()[0]) >= n
+
+
+def test_count_mode_on_dense_output(ej):
+    # whole clusters within epsilon: every 32 x 32 block of most tiles holds hits
+    X = datagen.generate(4, n=6000)
+    P = orc.decode(X)
+    eps = orc.select_eps_all_pairs(P, 900)
+    Xd = dev(X)
+    oc, ot = orc.selfjoin_count(P, eps)
+    counts, total = ej.selfjoin_count(Xd, eps)
+    pairs, _, found = run_pairs(ej, Xd, eps, capacity=int(ot * 1.1) + 8000, with_dist2=False)
+    counts = counts.cpu().numpy().view(np.uint32)
+    ns = pairs[pairs[:, 0] != pairs[:, 1]]
+    hist = np.bincount(ns[:, 0], minlength=6000) + np.bincount(ns[:, 1], minlength=6000)
+    assert np.array_equal(counts, hist) and int(total.cpu()[0]) == ns.shape[0]
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    st = parity.check_pair_sets(P, eps, pairs, None, ora_pairs, ora_d2)
+    assert abs(int(ot) - ns.shape[0]) <= st["only_gpu"] + st["only_oracle"]
