@@ -346,7 +346,8 @@ __device__ __forceinline__ void copy16_to_lds(uint32_t lds_addr, const void* sba
 // the counter reaches `expect` (workgroups per XCD x number of alignments so far).  Workgroups that
 // share operand panels only hit each other's lines in the XCD's L2 while they are within a few slices
 // of each other.  Purely a performance hint: the wait is bounded, so a grid that is not fully
-// resident cannot hang, and nothing depends on the counter's value.
+// resident cannot hang, and nothing depends on the counter's value.  A workgroup that has run out of
+// tiles adds 2^24, which satisfies every later expectation of the others.
 __device__ __forceinline__ void xcd_align(uint32_t* bar, uint32_t expect) {
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -465,7 +466,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   tc.init(blockIdx.x, gridDim.x, a.nsb, a.ntiles);
   uint32_t I = 0, J = 0, In = 0, Jn = 0;
   bool have = tc.next(I, J);
-  if (!have) return;
+  // a workgroup that leaves (now, or after its last tile) releases every later alignment of its XCD
+  auto xcd_leave = [&]() {
+    if (a.sync_mode >= 1 && tid == 0) __hip_atomic_fetch_add(a.xcd_bar + tc.xcd, 1u << 24, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  if (!have) {
+    xcd_leave();
+    return;
+  }
   bool have_next = tc.next(In, Jn);
   uint32_t epoch = 0, tiles_since_sync = 0;
   if (a.sync_mode >= 1) xcd_align(a.xcd_bar + tc.xcd, tc.wpx * ++epoch);
@@ -595,6 +603,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
+          if (__ballot(v[r] >= a.thr) == 0) continue;  // most registers of a flagged block hold no hit
           const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
           // rows/columns past n carry a large negative marker, which a huge epsilon can still reach: mask them here
           bool pass = v[r] >= a.thr && i < nn && j < nn;
@@ -640,6 +649,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       issue_on_next = false;  // the issue cursor, if it had moved on, is now on the current tile
     }
   }
+  xcd_leave();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the dump copies must land before the wave ends
   if (!COUNT) flush();
   if (COUNT && hits && lane == 0) atomicAdd(a.total, hits);
