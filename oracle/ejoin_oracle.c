@@ -213,3 +213,83 @@ int64_t orc_rows_join(const double *P, int64_t n, int32_t d, double eps2, const 
     }
     return row_start[R];
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Two-set join: "points" P (np x d) against "query points" Q (nq x d) -- the general form of the
+ * distance computation of Section 3.1 (fragments of points and of query points), of which the
+ * self-join is the case P = Q.  Result: every (i, j), i < np, j < nq, with D2(p_i, q_j) <= eps2,
+ * sorted by (i, j).  No symmetry, no self pairs: P and Q are different sets even when they hold
+ * equal points.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* counts_p[i] = #{ j : D2(p_i, q_j) <= eps2 }, counts_q[j] likewise (either may be NULL). Returns the total. */
+int64_t orc_join_count(const double *P, int64_t np, const double *Q, int64_t nq, int32_t d, double eps2,
+                       uint32_t *counts_p, uint32_t *counts_q)
+{
+    int64_t total = 0;
+#pragma omp parallel for schedule(dynamic, 64) reduction(+ : total)
+    for (int64_t i = 0; i < np; ++i) {
+        uint32_t c = 0;
+        for (int64_t j = 0; j < nq; ++j)
+            if (dist2_rows(P + i * (int64_t)d, Q + j * (int64_t)d, d) <= eps2)
+                ++c;
+        if (counts_p)
+            counts_p[i] = c;
+        total += c;
+    }
+    if (counts_q) {
+#pragma omp parallel for schedule(dynamic, 64)
+        for (int64_t j = 0; j < nq; ++j) {
+            uint32_t c = 0;
+            for (int64_t i = 0; i < np; ++i)
+                if (dist2_rows(P + i * (int64_t)d, Q + j * (int64_t)d, d) <= eps2)
+                    ++c;
+            counts_q[j] = c;
+        }
+    }
+    return total;
+}
+
+/* Pair list, sorted by (i, j); two passes like orc_selfjoin_pairs. row_start holds np + 1 entries. */
+int64_t orc_join_pairs(const double *P, int64_t np, const double *Q, int64_t nq, int32_t d, double eps2,
+                       uint32_t *pairs, double *d2out, int64_t capacity, int64_t *row_start)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < np; ++i) {
+        int64_t c = 0;
+        for (int64_t j = 0; j < nq; ++j)
+            if (dist2_rows(P + i * (int64_t)d, Q + j * (int64_t)d, d) <= eps2)
+                ++c;
+        row_start[i + 1] = c;
+    }
+    row_start[0] = 0;
+    for (int64_t i = 0; i < np; ++i)
+        row_start[i + 1] += row_start[i];
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < np; ++i) {
+        int64_t pos = row_start[i];
+        for (int64_t j = 0; j < nq; ++j) {
+            double v = dist2_rows(P + i * (int64_t)d, Q + j * (int64_t)d, d);
+            if (v <= eps2) {
+                if (pos < capacity) {
+                    pairs[2 * pos] = (uint32_t)i;
+                    pairs[2 * pos + 1] = (uint32_t)j;
+                    if (d2out)
+                        d2out[pos] = v;
+                }
+                ++pos;
+            }
+        }
+    }
+    return row_start[np];
+}
+
+/* Dense block between the two sets: out[r * cols + c] = D2(p_{i0+r}, q_{j0+c}). */
+void orc_dist2_block2(const double *P, const double *Q, int32_t d, int64_t i0, int32_t rows, int64_t j0, int32_t cols,
+                      double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t r = 0; r < rows; ++r)
+        for (int32_t c = 0; c < cols; ++c)
+            out[(int64_t)r * cols + c] = dist2_rows(P + (i0 + r) * (int64_t)d, Q + (j0 + c) * (int64_t)d, d);
+}

@@ -68,6 +68,12 @@ def _L():
         lib.orc_selfjoin_pairs.argtypes = [p, C.c_int64, C.c_int32, C.c_double, p, p, C.c_int64, p]
         lib.orc_rows_join.restype = C.c_int64
         lib.orc_rows_join.argtypes = [p, C.c_int64, C.c_int32, C.c_double, p, C.c_int64, p, p, p]
+        lib.orc_join_count.restype = C.c_int64
+        lib.orc_join_count.argtypes = [p, C.c_int64, p, C.c_int64, C.c_int32, C.c_double, p, p]
+        lib.orc_join_pairs.restype = C.c_int64
+        lib.orc_join_pairs.argtypes = [p, C.c_int64, p, C.c_int64, C.c_int32, C.c_double, p, p, C.c_int64, p]
+        lib.orc_dist2_block2.restype = None
+        lib.orc_dist2_block2.argtypes = [p, p, C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_int32, p]
         _lib = lib
     return _lib
 
@@ -160,6 +166,36 @@ def rows_join(P: np.ndarray, eps, rows: np.ndarray) -> tuple[np.ndarray, np.ndar
     d2 = np.empty(total, dtype=np.float64)
     _L().orc_rows_join(_ptr(P), n, d, e2, _ptr(rows), R, _ptr(row_start), _ptr(nbr), _ptr(d2))
     return row_start, nbr, d2
+
+
+def join_count(P: np.ndarray, Q: np.ndarray, eps) -> tuple[np.ndarray, np.ndarray, int]:
+    """Two-set join: (counts_p[i] = matches of p_i in Q, counts_q[j] = matches of q_j in P, total)."""
+    assert P.shape[1] == Q.shape[1]
+    cp = np.empty(P.shape[0], dtype=np.uint32)
+    cq = np.empty(Q.shape[0], dtype=np.uint32)
+    total = _L().orc_join_count(_ptr(P), P.shape[0], _ptr(Q), Q.shape[0], P.shape[1], eps2_of(eps), _ptr(cp), _ptr(cq))
+    return cp, cq, int(total)
+
+
+def join_pairs(P: np.ndarray, Q: np.ndarray, eps) -> tuple[np.ndarray, np.ndarray]:
+    """Two-set join: (pairs (m, 2) uint32 sorted by (i, j), i indexes P and j indexes Q; D2 (m,))."""
+    assert P.shape[1] == Q.shape[1]
+    n_p, d = P.shape
+    row_start = np.empty(n_p + 1, dtype=np.int64)
+    e2 = eps2_of(eps)
+    found = _L().orc_join_pairs(_ptr(P), n_p, _ptr(Q), Q.shape[0], d, e2, None, None, 0, _ptr(row_start))
+    pairs = np.empty((found, 2), dtype=np.uint32)
+    d2 = np.empty(found, dtype=np.float64)
+    again = _L().orc_join_pairs(_ptr(P), n_p, _ptr(Q), Q.shape[0], d, e2, _ptr(pairs), _ptr(d2), found, _ptr(row_start))
+    assert again == found
+    return pairs, d2
+
+
+def dist2_block2(P: np.ndarray, Q: np.ndarray, i0: int, rows: int, j0: int, cols: int) -> np.ndarray:
+    assert 0 <= i0 and i0 + rows <= P.shape[0] and 0 <= j0 and j0 + cols <= Q.shape[0]
+    out = np.empty((rows, cols), dtype=np.float64)
+    _L().orc_dist2_block2(_ptr(P), _ptr(Q), P.shape[1], i0, rows, j0, cols, _ptr(out))
+    return out
 
 
 # ---------------------------------------------------------------------------------------------

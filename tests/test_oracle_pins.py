@@ -232,3 +232,60 @@ def test_boundary_band_overlap_and_error_stats():
     assert orc.overlap_accuracy(3, a, a) == 1.0
     m, s = orc.distance_error_stats(np.array([4.0, 9.0]), np.array([1.0, 16.0]))
     assert m == pytest.approx(0.0) and s == pytest.approx(1.0)
+
+
+# ------------------------------------------------------------------ two-set join
+def test_two_set_join_against_python_loop_and_rational_arithmetic():
+    rng = np.random.default_rng(21)
+    XP = rng.standard_normal((23, 40)).astype(np.float16).view(np.uint16)
+    XQ = rng.standard_normal((17, 40)).astype(np.float16).view(np.uint16)
+    XQ[5] = XP[11]  # an exact duplicate across the sets: distance 0, must match for eps = 0
+    P, Q = orc.decode(XP), orc.decode(XQ)
+    FP, FQ = _frac_rows(XP), _frac_rows(XQ)
+    B = orc.dist2_block2(P, Q, 0, 23, 0, 17)
+    for i in range(23):
+        for j in range(17):
+            exact = sum((a - b) ** 2 for a, b in zip(FP[i], FQ[j]))
+            assert abs(Fraction(B[i, j]) - exact) <= exact * Fraction(40, 2**52)
+    assert B[11, 5] == 0.0
+    pairs, d2 = orc.join_pairs(P, Q, 0.0)
+    assert pairs.tolist() == [[11, 5]] and d2.tolist() == [0.0]
+    eps = np.float32(np.sqrt(np.sort(B.ravel())[60]))
+    e2 = float(eps) ** 2
+    want = [(i, j) for i in range(23) for j in range(17) if B[i, j] <= e2]
+    pairs, d2 = orc.join_pairs(P, Q, eps)
+    assert [tuple(p) for p in pairs.tolist()] == want and np.array_equal(d2, B[pairs[:, 0], pairs[:, 1]])
+    cp, cq, total = orc.join_count(P, Q, eps)
+    assert total == len(want)
+    assert np.array_equal(cp, np.bincount(pairs[:, 0], minlength=23)) and np.array_equal(cq, np.bincount(pairs[:, 1], minlength=17))
+    assert np.array_equal(orc.dist2_block2(P, Q, 3, 4, 2, 9), B[3:7, 2:11])
+
+
+def test_two_set_join_closed_form_shifted_lattices():
+    # P: x = t*h, Q: x = u*h + h/2 on a line; |p_t - q_u| = |t - u - 1/2| h
+    h, n_p, n_q = 0.25, 40, 33
+    XP = datagen.lattice_points(n_p, 4, h)
+    q = np.zeros((n_q, 4), dtype=np.float16)
+    q[:, 0] = np.arange(n_q) * h + h / 2
+    XQ = q.view(np.uint16)
+    P, Q = orc.decode(XP), orc.decode(XQ)
+    for eps in [0.1, 0.125, 0.3, 0.375, 1.0, 100.0]:
+        e = float(np.float32(eps))
+        want = [(t, u) for t in range(n_p) for u in range(n_q) if abs(t - u - 0.5) * h <= e]
+        pairs, _ = orc.join_pairs(P, Q, eps)
+        assert [tuple(p) for p in pairs.tolist()] == want
+        assert orc.join_count(P, Q, eps)[2] == len(want)
+
+
+def test_two_set_join_of_a_set_with_itself_is_the_full_self_join():
+    X = datagen.generate(2, n=120)
+    P = orc.decode(X)
+    eps = orc.select_eps_all_pairs(P, 8)
+    sp, _ = orc.selfjoin_pairs(P, eps)  # i <= j, self pairs included
+    jp, _ = orc.join_pairs(P, P, eps)   # all ordered pairs
+    ns = sp[sp[:, 0] != sp[:, 1]]
+    want = sorted([tuple(p) for p in sp.tolist()] + [(j, i) for i, j in ns.tolist()])
+    assert [tuple(p) for p in jp.tolist()] == want
+    cp, cq, total = orc.join_count(P, P, eps)
+    counts, t_self = orc.selfjoin_count(P, eps)
+    assert total == 2 * t_self + 120 and np.array_equal(cp, counts + 1) and np.array_equal(cq, cp)
