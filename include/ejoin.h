@@ -58,7 +58,8 @@ int ejoin_create(ejoin_ctx** out, int device);
 /* Free the context and its device memory.  The caller must have synchronised its streams. */
 int ejoin_destroy(ejoin_ctx* ctx);
 
-/* Grow the workspace so that joins of up to n points of up to d coordinates allocate nothing. */
+/* Grow the workspace so that joins of up to n points in total (both sets of a two-set join
+ * together) of up to d coordinates allocate nothing. */
 int ejoin_reserve(ejoin_ctx* ctx, int64_t n, int32_t d);
 
 /* Static, human-readable text for a return code. */
@@ -88,6 +89,23 @@ int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
 int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
                          uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
 
+/* Two-set join: "points" P (np x d) against "query points" Q (nq x d), the general form of the
+ * distance computation of Section 3.1 (fragments of points and of query points; the paper offers
+ * the method as a subroutine for such searches, Section 1).  Same layout rules for P and Q as for X
+ * (own row strides ldp, ldq; same d).  Result: every (i, j), i < np, j < nq, with dist(p_i, q_j) <= eps,
+ * once, as pairs[2p] = i (index into P), pairs[2p+1] = j (index into Q); no symmetry is assumed and
+ * there are no self pairs.  capacity / n_pairs / dist2 as for ejoin_selfjoin_pairs.
+ * The data-range rule (s < 2^31) applies to both sets. */
+int ejoin_join_pairs(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq,
+                     int32_t d, float eps, uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
+
+/* Counts of the two-set join:
+ *   counts_p[i] (device, np x u32, overwritten) = #{ j : dist(p_i, q_j) <= eps }
+ *   counts_q[j] (device, nq x u32, overwritten; may be NULL) = #{ i : dist(p_i, q_j) <= eps }
+ *   *total      (device, u64, overwritten)      = number of matching (i, j) */
+int ejoin_join_count(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq,
+                     int32_t d, float eps, uint32_t* counts_p, uint32_t* counts_q, uint64_t* total, void* stream);
+
 /* Dense block of squared distances, for checking Steps 2-3 of Section 3.1 element by element:
  *   out[r * cols + c] = d2(i0 + r, j0 + c),  0 <= r < rows, 0 <= c < cols   (device, rows*cols f32)
  * computed with exactly the arithmetic of the join (so it is bit-identical to the dist2 the join
@@ -113,6 +131,8 @@ int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* norms_ms, float* join_ms);
 /* Number of 256 x 256 output tiles the Gram kernel evaluates for n points (upper triangle,
  * diagonal included): the executed matrix-core work is 2 * 256 * 256 * roundup(d,64) FLOP per tile. */
 int64_t ejoin_tiles_evaluated(int64_t n);
+/* ... and for a two-set join of np x nq points (the full grid of tiles). */
+int64_t ejoin_tiles_evaluated2(int64_t np, int64_t nq);
 
 #ifdef __cplusplus
 }

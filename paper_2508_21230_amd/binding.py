@@ -46,6 +46,12 @@ def load_library() -> C.CDLL:
     lib.ejoin_selfjoin_count.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
     lib.ejoin_selfjoin_pairs.restype = C.c_int
     lib.ejoin_selfjoin_pairs.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_join_pairs.restype = C.c_int
+    lib.ejoin_join_pairs.argtypes = [vp, vp, i64, i64, vp, i64, i64, i32, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_join_count.restype = C.c_int
+    lib.ejoin_join_count.argtypes = [vp, vp, i64, i64, vp, i64, i64, i32, f32, vp, vp, vp, vp]
+    lib.ejoin_tiles_evaluated2.restype = i64
+    lib.ejoin_tiles_evaluated2.argtypes = [i64, i64]
     lib.ejoin_dist2_tile.restype = C.c_int
     lib.ejoin_dist2_tile.argtypes = [vp, vp, i64, i32, i64, i64, i64, i32, i32, vp, vp]
     lib.ejoin_status.restype = C.c_int
@@ -62,6 +68,10 @@ def load_library() -> C.CDLL:
 
 def tiles_evaluated(n: int) -> int:
     return int(load_library().ejoin_tiles_evaluated(int(n)))
+
+
+def tiles_evaluated2(n_p: int, n_q: int) -> int:
+    return int(load_library().ejoin_tiles_evaluated2(int(n_p), int(n_q)))
 
 
 class EJoin:
@@ -144,6 +154,38 @@ class EJoin:
                                                    dist2.data_ptr() if dist2 is not None else None, capacity,
                                                    n_pairs.data_ptr(), self._stream()), self._h)
         return pairs, dist2, n_pairs
+
+    def join_pairs(self, P: torch.Tensor, Q: torch.Tensor, eps: float, capacity: int, d: int | None = None, with_dist2: bool = True,
+                   pairs: torch.Tensor | None = None, dist2: torch.Tensor | None = None, n_pairs: torch.Tensor | None = None):
+        """Two-set join; returns (pairs int32[capacity, 2]: (index into P, index into Q), dist2 or None, n_pairs int64[1])."""
+        n_p, d_p, ldp = self._x(P, d)
+        n_q, d_q, ldq = self._x(Q, d)
+        if d_p != d_q:
+            raise EJoinError("P and Q must have the same number of coordinates")
+        capacity = int(capacity)
+        if pairs is None:
+            pairs = torch.empty((max(capacity, 1), 2), dtype=torch.int32, device=P.device)
+        if dist2 is None and with_dist2:
+            dist2 = torch.empty(max(capacity, 1), dtype=torch.float32, device=P.device)
+        if n_pairs is None:
+            n_pairs = torch.empty(1, dtype=torch.int64, device=P.device)
+        self._check(self._lib.ejoin_join_pairs(self._h, P.data_ptr(), n_p, ldp, Q.data_ptr(), n_q, ldq, d_p, float(eps), pairs.data_ptr(),
+                                               dist2.data_ptr() if dist2 is not None else None, capacity, n_pairs.data_ptr(),
+                                               self._stream()), self._h)
+        return pairs, dist2, n_pairs
+
+    def join_count(self, P: torch.Tensor, Q: torch.Tensor, eps: float, d: int | None = None, want_counts_q: bool = True):
+        """Two-set join counts; returns (counts_p int32[np], counts_q int32[nq] or None, total int64[1])."""
+        n_p, d_p, ldp = self._x(P, d)
+        n_q, d_q, ldq = self._x(Q, d)
+        if d_p != d_q:
+            raise EJoinError("P and Q must have the same number of coordinates")
+        cp = torch.empty(n_p, dtype=torch.int32, device=P.device)
+        cq = torch.empty(n_q, dtype=torch.int32, device=P.device) if want_counts_q else None
+        total = torch.empty(1, dtype=torch.int64, device=P.device)
+        self._check(self._lib.ejoin_join_count(self._h, P.data_ptr(), n_p, ldp, Q.data_ptr(), n_q, ldq, d_p, float(eps), cp.data_ptr(),
+                                               cq.data_ptr() if cq is not None else None, total.data_ptr(), self._stream()), self._h)
+        return cp, cq, total
 
     def dist2_tile(self, X: torch.Tensor, i0: int, j0: int, rows: int, cols: int, d: int | None = None) -> torch.Tensor:
         n, d, ld = self._x(X, d)

@@ -55,21 +55,25 @@ constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
 __host__ __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 
 struct JoinArgs {
-  const uint4* Xp;         // packed copy of X plus the augmentation block, see k_pack / k_aux
-  int64_t npad;            // rows of Xp per k-block: n rounded up to a multiple of TILE
+  // "points" (rows of the distance matrix) and "query points" (columns); the self-join passes the same set twice
+  const uint4* XpA;        // packed copy of the points plus their augmentation block, see k_pack / k_aux
+  const uint4* XpB;        // ... of the query points
+  int64_t npadA, npadB;    // rows per k-block: the set's size rounded up to a multiple of TILE
+  int64_t nA, nB;
+  int self;                // 1: self-join (upper triangle, self pairs), 0: two different sets (full rectangle)
   const uint32_t* status;  // device status word
-  int64_t n;
-  int nslices;  // roundup(d, 64) / 32 : k-blocks of X (the augmentation block follows them)
+  int nslices;  // roundup(d, 64) / 32 : k-blocks of data (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
-  uint32_t ntiles;  // ceil(n / TILE)
-  uint32_t nsb;     // ceil(ntiles / SB)
+  uint32_t ntilesA, ntilesB;  // ceil(n / TILE)
+  uint32_t nsbA, nsbB;        // ceil(ntiles / SB)
   // pair mode
   uint32_t* pairs;
   float* dist2;
   unsigned long long capacity;
   unsigned long long* n_pairs;
   // count mode
-  uint32_t* counts;
+  uint32_t* counts;    // per point (self-join: per point of the one set)
+  uint32_t* counts_b;  // per query point (two-set join only; may be null)
   unsigned long long* total;
   // XCD-wide alignment of the workgroups (performance hint, see xcd_align)
   uint32_t* xcd_bar;  // NUM_XCD counters, zeroed before the launch
@@ -272,26 +276,31 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
 //     hit rate collapses (measured: 16 % instead of ~75 %).
 struct TileCursor {
   uint32_t xcd, wpx;     // this workgroup's XCD; workgroups per XCD
-  uint32_t nsb, ntiles;
+  uint32_t self, nsbA, nsbB, ntA, ntB;
   uint64_t target;       // position of this workgroup's next tile in the XCD's list
   uint64_t rank0;        // position of the first non-empty tile of the current super-block's rectangle
-  uint32_t P, Q, sbi;    // current super-block: coordinates (P <= Q) and linear index
-  __device__ void init(uint32_t block, uint32_t nblocks, uint32_t nsb_, uint32_t ntiles_) {
+  uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
+  __device__ void init(uint32_t block, uint32_t nblocks, const JoinArgs& a) {
     xcd = block % NUM_XCD;
     wpx = (nblocks - xcd + NUM_XCD - 1) / NUM_XCD;  // workgroups with this XCD id
-    nsb = nsb_;
-    ntiles = ntiles_;
+    self = a.self;
+    nsbA = a.nsbA;
+    nsbB = a.nsbB;
+    ntA = a.ntilesA;
+    ntB = a.ntilesB;
     target = block / NUM_XCD;
     rank0 = 0;
     P = Q = sbi = 0;
   }
-  __device__ bool cell_ok(uint32_t I, uint32_t J) const { return I <= J && J < ntiles; }
+  // self-join: upper triangle (I <= J); two sets: the whole ntA x ntB grid
+  __device__ bool cell_ok(uint32_t I, uint32_t J) const { return self ? (I <= J && J < ntB) : (I < ntA && J < ntB); }
   // next tile of this workgroup; false when the work is exhausted
   __device__ bool next(uint32_t& I, uint32_t& J) {
-    while (P < nsb) {
+    while (P < nsbA) {
       const uint32_t xp = (xcd + sbi) & 7;
       const uint32_t I0 = P * SB + (xp >> 2) * 8, J0 = Q * SB + (xp & 3) * 4;
-      const bool special = (P == Q) || (J0 + 4 > ntiles);  // rectangle may hold empty cells
+      // may the rectangle hold empty cells?
+      const bool special = self ? ((P == Q) || (J0 + 4 > ntB)) : ((I0 + 8 > ntA) || (J0 + 4 > ntB));
       uint32_t v = 32;
       if (special) {
         v = 0;
@@ -311,9 +320,9 @@ struct TileCursor {
       }
       rank0 += v;
       ++sbi;
-      if (++Q == nsb) {
+      if (++Q == nsbB) {  // super-blocks row-major; the self-join starts each row on the diagonal
         ++P;
-        Q = P;
+        Q = self ? P : 0;
       }
     }
     return false;
@@ -375,8 +384,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // panel; in the packed layout that is 1 KB of contiguous global memory.  Wave w copies blocks w and
   // w + 8 of both 16 KB panels of a slice: 4 copy instructions per wave and slice, always (past the
   // end of the work they are pointed at a dump area), so the number of outstanding copies is a constant.
-  const char* Xb = reinterpret_cast<const char*>(a.Xp);
-  const int64_t kstride = a.npad * 64;  // bytes from one k-block of Xp to the next
+  const char* XbA = reinterpret_cast<const char*>(a.XpA);
+  const char* XbB = reinterpret_cast<const char*>(a.XpB);
+  const int64_t kstrideA = a.npadA * 64, kstrideB = a.npadB * 64;  // bytes from one k-block to the next
   const uint32_t voff0 = lane * 16 + wave * 1024, voff1 = voff0 + 8192;
   auto issue_slice = [&](const char* pa, const char* pb, uint32_t lds_stage /* LDS address of the stage + wave*1024 */) {
     copy16_to_lds<0>(lds_stage, pa, voff0);
@@ -463,7 +473,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 
   // ---------------- prologue
   TileCursor tc;
-  tc.init(blockIdx.x, gridDim.x, a.nsb, a.ntiles);
+  tc.init(blockIdx.x, gridDim.x, a);
   uint32_t I = 0, J = 0, In = 0, Jn = 0;
   bool have = tc.next(I, J);
   // a workgroup that leaves (now, or after its last tile) releases every later alignment of its XCD
@@ -484,25 +494,25 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   int iks = 0;
   bool issue_live = true;       // the issue cursor still points at real work
   bool issue_on_next = false;   // ... of the tile after the one being computed
-  const char* pa = Xb + (int64_t)I * (TILE * 64);
-  const char* pb = Xb + (int64_t)J * (TILE * 64);
+  const char* pa = XbA + (int64_t)I * (TILE * 64);
+  const char* pb = XbB + (int64_t)J * (TILE * 64);
   const uint32_t lds_w = lds0 + wave * 1024;
   auto issue_one = [&](uint32_t Gissue) {
     if (issue_live) {
       issue_slice(pa, pb, lds_w + (Gissue % NSTAGE) * STAGE_BYTES);
     } else {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, Xb, lane * 16);
+      for (int q = 0; q < 4; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, XbA, lane * 16);
     }
-    pa += kstride;
-    pb += kstride;
+    pa += kstrideA;
+    pb += kstrideB;
     if (++iks == nslT) {
       iks = 0;
       const bool to_next = issue_live && !issue_on_next && have_next;
       issue_live = to_next;
       issue_on_next = to_next;
-      pa = Xb + (int64_t)(to_next ? In : 0) * (TILE * 64);
-      pb = Xb + (int64_t)(to_next ? Jn : 0) * (TILE * 64);
+      pa = XbA + (int64_t)(to_next ? In : 0) * (TILE * 64);
+      pb = XbB + (int64_t)(to_next ? Jn : 0) * (TILE * 64);
     }
   };
   for (int q = 0; q < DIST; ++q) issue_one(q);
@@ -554,7 +564,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     {
       // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of tile (mt, nt) in lane l is the pair
       //   i = I*256 + wm*128 + mt*32 + 8*(r/4) + 4*(l/32) + r%4 ,  j = J*256 + wn*64 + nt*32 + l%32.
-      const bool diag = (I == J);
+      const bool diag = a.self && (I == J);
       // a wave tile of a diagonal block that lies entirely below the diagonal holds no pair i <= j
       const bool skip = diag && (wm * 128 >= wn * 64 + 64);
       // cheap filter: which of the eight 32 x 32 blocks of this wave tile hold a passing pair at all
@@ -598,7 +608,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
           default: v = acc[3][1]; break;
         }
         const int mt = b >> 1, nt = b & 1;
-        const uint32_t nn = (uint32_t)a.n;
+        const uint32_t nnA = (uint32_t)a.nA, nnB = (uint32_t)a.nB;
         const uint32_t j = J * TILE + wn * 64 + nt * 32 + r32;
         const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
 #pragma unroll
@@ -606,7 +616,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
           if (__ballot(v[r] >= a.thr) == 0) continue;  // most registers of a flagged block hold no hit
           const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
           // rows/columns past n carry a large negative marker, which a huge epsilon can still reach: mask them here
-          bool pass = v[r] >= a.thr && i < nn && j < nn;
+          bool pass = v[r] >= a.thr && i < nnA && j < nnB;
           if (diag) pass = pass && (COUNT ? i < j : i <= j);
           const unsigned long long mask = __ballot(pass);
           if (mask) {
@@ -614,7 +624,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
             if (COUNT) {
               if (pass) {
                 atomicAdd(&a.counts[i], 1u);
-                atomicAdd(&a.counts[j], 1u);
+                if (a.self) atomicAdd(&a.counts[j], 1u);
+                else if (a.counts_b) atomicAdd(&a.counts_b[j], 1u);
               }
               hits += cnt;
               dirty = true;
@@ -702,9 +713,10 @@ int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int6
 int64_t pad_rows(int64_t n) { return (n + TILE - 1) / TILE * TILE; }
 int64_t pad_dims(int32_t d) { return ((int64_t)d + KPAD - 1) / KPAD * KPAD; }
 
-// d = 0: only the per-point arrays (norms, augmentation rows); d > 0: also the packed copy of X.
-int ensure_workspace(ejoin_ctx* ctx, int64_t n, int32_t d) {
-  if (n > ctx->s_cap) {
+// Workspace for `rows` points in total (each set padded to a multiple of TILE).
+// d = 0: only the per-point arrays (norms, augmentation rows); d > 0: also the packed copies.
+int ensure_workspace(ejoin_ctx* ctx, int64_t rows, int32_t d) {
+  if (rows > ctx->s_cap) {
     if (ctx->s || ctx->H) {
       EJ_TRY(hipDeviceSynchronize());
       if (ctx->s) EJ_TRY(hipFree(ctx->s));
@@ -713,8 +725,8 @@ int ensure_workspace(ejoin_ctx* ctx, int64_t n, int32_t d) {
       ctx->H = nullptr;
       ctx->s_cap = 0;
     }
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->s), (size_t)n * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->H), (size_t)pad_rows(n) * sizeof(uint4));
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->s), (size_t)rows * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->H), (size_t)rows * sizeof(uint4));
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (ctx->s) (void)hipFree(ctx->s);
@@ -722,9 +734,9 @@ int ensure_workspace(ejoin_ctx* ctx, int64_t n, int32_t d) {
       if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
       return fail_hip(ctx, e, "hipMalloc(workspace)");
     }
-    ctx->s_cap = n;
+    ctx->s_cap = rows;
   }
-  const int64_t need = d > 0 ? pad_rows(n) * (pad_dims(d) + KSLICE) * 2 : 0;  // data k-blocks + the augmentation block
+  const int64_t need = d > 0 ? rows * (pad_dims(d) + KSLICE) * 2 : 0;  // data k-blocks + the augmentation block
   if (need > ctx->xp_bytes) {
     if (ctx->Xp) {
       EJ_TRY(hipDeviceSynchronize());
@@ -753,16 +765,24 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
   return EJOIN_OK;
 }
 
-// Steps shared by the join and the dense-tile call: reset, norms (+ max), augmentation rows.
-// aug: where the join wants the augmentation k-block (null for the dense-tile call).
-int launch_prepare(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, unsigned long long* counter, uint4* aug,
-                   hipStream_t st) {
+int launch_reset(ejoin_ctx* ctx, unsigned long long* counter, hipStream_t st) {
   hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctx->status, counter);
   EJ_TRY(hipGetLastError());
-  int rc = launch_norms(ctx, X, n, d, ld, ctx->s, ctx->status + 1, st);
-  if (rc != EJOIN_OK) return rc;
+  return EJOIN_OK;
+}
+
+// Augmentation rows of one set from its norms and the running maximum of all norms.
+// aug: where the join wants the set's augmentation k-block (null for the dense-tile call).
+int launch_aux(ejoin_ctx* ctx, const float* s, int64_t n, uint4* H, uint4* aug, hipStream_t st) {
   const int64_t npad = pad_rows(n);
-  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, ctx->s, n, npad, ctx->status, ctx->H, aug);
+  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, s, n, npad, ctx->status, H, aug);
+  EJ_TRY(hipGetLastError());
+  return EJOIN_OK;
+}
+
+int launch_pack(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int64_t ld, int nkb, uint4* Xp, hipStream_t st) {
+  const int64_t chunks = (int64_t)nkb * pad_rows(n) * 4;
+  hipLaunchKernelGGL(k_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X, n, pad_rows(n), ld, nkb, Xp);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -780,26 +800,44 @@ struct DeviceGuard {
   }
 };
 
+// XB == nullptr: self-join of XA.
 template <bool COUNT>
-int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs, float* dist2,
-             uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint64_t* total, hipStream_t st) {
-  int rc = ensure_workspace(ctx, n, d);
+int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const uint16_t* XB, int64_t nB, int64_t ldB, int32_t d,
+             float eps, uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint32_t* counts_b,
+             uint64_t* total, hipStream_t st) {
+  const bool self = (XB == nullptr);
+  const int64_t padA = pad_rows(nA), padB = self ? 0 : pad_rows(nB);
+  int rc = ensure_workspace(ctx, padA + padB, d);
   if (rc != EJOIN_OK) return rc;
+  const int nkb = (d + KPAD - 1) / KPAD * (KPAD / KSLICE);
+  float* sA = ctx->s;
+  float* sB = ctx->s + padA;
+  uint4* HA = ctx->H;
+  uint4* HB = ctx->H + padA;
+  uint4* XpA = ctx->Xp;
+  uint4* XpB = ctx->Xp + padA * (int64_t)(nkb + 1) * 4;
   JoinArgs a;
   memset(&a, 0, sizeof(a));
-  a.Xp = ctx->Xp;
-  a.npad = pad_rows(n);
+  a.XpA = XpA;
+  a.XpB = self ? XpA : XpB;
+  a.npadA = padA;
+  a.npadB = self ? padA : padB;
+  a.nA = nA;
+  a.nB = self ? nA : nB;
+  a.self = self ? 1 : 0;
   a.status = ctx->status;
-  a.n = n;
-  a.nslices = (d + KPAD - 1) / KPAD * (KPAD / KSLICE);
+  a.nslices = nkb;
   a.thr = -0.5f * (eps * eps);
-  a.ntiles = (uint32_t)((n + TILE - 1) / TILE);
-  a.nsb = (a.ntiles + SB - 1) / SB;
+  a.ntilesA = (uint32_t)(padA / TILE);
+  a.ntilesB = (uint32_t)(a.npadB / TILE);
+  a.nsbA = (a.ntilesA + SB - 1) / SB;
+  a.nsbB = (a.ntilesB + SB - 1) / SB;
   a.pairs = pairs;
   a.dist2 = dist2;
   a.capacity = capacity;
   a.n_pairs = reinterpret_cast<unsigned long long*>(n_pairs);
   a.counts = counts;
+  a.counts_b = counts_b;
   a.total = reinterpret_cast<unsigned long long*>(total);
   a.xcd_bar = ctx->status + 8;
   {
@@ -810,17 +848,21 @@ int run_join(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld
   }
 
   if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
-  rc = launch_prepare(ctx, X, n, d, ld, COUNT ? a.total : a.n_pairs, ctx->Xp + (int64_t)a.nslices * a.npad * 4, st);
-  if (rc != EJOIN_OK) return rc;
-  {
-    const int nkb = a.nslices;
-    const int64_t chunks = (int64_t)nkb * a.npad * 4;
-    hipLaunchKernelGGL(k_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X, n, a.npad, ld, nkb, ctx->Xp);
-    EJ_TRY(hipGetLastError());
-  }
+  if ((rc = launch_reset(ctx, COUNT ? a.total : a.n_pairs, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_norms(ctx, XA, nA, d, ldA, sA, ctx->status + 1, st)) != EJOIN_OK) return rc;
+  if (!self && (rc = launch_norms(ctx, XB, nB, d, ldB, sB, ctx->status + 1, st)) != EJOIN_OK) return rc;
+  // the augmentation rows need the maximum over both sets, so they follow both norm kernels
+  if ((rc = launch_aux(ctx, sA, nA, HA, XpA + (int64_t)nkb * padA * 4, st)) != EJOIN_OK) return rc;
+  if (!self && (rc = launch_aux(ctx, sB, nB, HB, XpB + (int64_t)nkb * padB * 4, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_pack(ctx, XA, nA, ldA, nkb, XpA, st)) != EJOIN_OK) return rc;
+  if (!self && (rc = launch_pack(ctx, XB, nB, ldB, nkb, XpB, st)) != EJOIN_OK) return rc;
   if (COUNT) {
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counts, n, 0u);
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nA + 255) / 256)), dim3(256), 0, st, counts, nA, 0u);
     EJ_TRY(hipGetLastError());
+    if (counts_b) {
+      hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nB + 255) / 256)), dim3(256), 0, st, counts_b, nB, 0u);
+      EJ_TRY(hipGetLastError());
+    }
   }
   if (ctx->profiling) {
     EJ_TRY(hipEventRecord(ctx->ev[1], st));
@@ -894,7 +936,7 @@ int ejoin_reserve(ejoin_ctx* ctx, int64_t n, int32_t d) {
   if (!ctx || n < 1 || d < 1 || d > 65536) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return ensure_workspace(ctx, n, d);
+  return ensure_workspace(ctx, pad_rows(n) + TILE, d);  // + TILE: a total split over two sets pads each of them
 }
 
 const char* ejoin_strerror(int code) {
@@ -926,7 +968,8 @@ int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
   if (!counts || !total_pairs || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return run_join<true>(ctx, X, n, d, ld, eps, nullptr, nullptr, 0, nullptr, counts, total_pairs, static_cast<hipStream_t>(stream));
+  return run_join<true>(ctx, X, n, ld, nullptr, 0, 0, d, eps, nullptr, nullptr, 0, nullptr, counts, nullptr, total_pairs,
+                        static_cast<hipStream_t>(stream));
 }
 
 int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs,
@@ -936,7 +979,32 @@ int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
   if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return run_join<false>(ctx, X, n, d, ld, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, static_cast<hipStream_t>(stream));
+  return run_join<false>(ctx, X, n, ld, nullptr, 0, 0, d, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
+                         static_cast<hipStream_t>(stream));
+}
+
+int ejoin_join_pairs(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq, int32_t d,
+                     float eps, uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
+  int rc = check_common(ctx, P, np, d, ldp);
+  if (rc == EJOIN_OK) rc = check_common(ctx, Q, nq, d, ldq);
+  if (rc != EJOIN_OK) return rc;
+  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join<false>(ctx, P, np, ldp, Q, nq, ldq, d, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
+                         static_cast<hipStream_t>(stream));
+}
+
+int ejoin_join_count(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq, int32_t d,
+                     float eps, uint32_t* counts_p, uint32_t* counts_q, uint64_t* total, void* stream) {
+  int rc = check_common(ctx, P, np, d, ldp);
+  if (rc == EJOIN_OK) rc = check_common(ctx, Q, nq, d, ldq);
+  if (rc != EJOIN_OK) return rc;
+  if (!counts_p || !total || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join<true>(ctx, P, np, ldp, Q, nq, ldq, d, eps, nullptr, nullptr, 0, nullptr, counts_p, counts_q, total,
+                        static_cast<hipStream_t>(stream));
 }
 
 int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, int64_t i0, int64_t j0, int32_t rows,
@@ -947,11 +1015,12 @@ int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   if (rows > 32 * 65535 || cols > 32 * 65535) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  rc = ensure_workspace(ctx, n, 0);
+  rc = ensure_workspace(ctx, pad_rows(n), 0);
   if (rc != EJOIN_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  rc = launch_prepare(ctx, X, n, d, ld, nullptr, nullptr, st);
-  if (rc != EJOIN_OK) return rc;
+  if ((rc = launch_reset(ctx, nullptr, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_norms(ctx, X, n, d, ld, ctx->s, ctx->status + 1, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, nullptr, st)) != EJOIN_OK) return rc;
   hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->H, ctx->status, n, ld, k16_steps(d), i0, j0, rows, cols, out);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
@@ -991,6 +1060,11 @@ int64_t ejoin_tiles_evaluated(int64_t n) {
   if (n < 1) return 0;
   const int64_t t = (n + TILE - 1) / TILE;
   return t * (t + 1) / 2;
+}
+
+int64_t ejoin_tiles_evaluated2(int64_t np, int64_t nq) {
+  if (np < 1 || nq < 1) return 0;
+  return ((np + TILE - 1) / TILE) * ((nq + TILE - 1) / TILE);
 }
 
 }  // extern "C"
