@@ -57,7 +57,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=3, help="workload id 1..5 (datagen.WORKLOADS)")
     ap.add_argument("--selectivity", type=int, default=None)
-    ap.add_argument("--mode", choices=["pairs", "count"], default="pairs")
+    ap.add_argument("--mode", choices=["pairs", "count", "join"], default="pairs",
+                    help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points")
+    ap.add_argument("--queries", type=int, default=100_000, help="query points of --mode join (same distribution, rows n .. n+queries-1)")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None)
@@ -78,13 +80,20 @@ def main():
     n = args.n or spec["n"]
     d = spec["d"]
     eps = load_eps(w, S)
-    X = datagen.generate(w, n=n)
-    Xd = torch.from_numpy(X.view(np.int16)).to("cuda:0")
+    nq = args.queries if args.mode == "join" else 0
+    X = datagen.generate(w, n=n + nq)
+    Xd = torch.from_numpy(X[:n].view(np.int16)).to("cuda:0")
     ej = pkg.EJoin(0)
-    ej.reserve(n, d)
-    expect_pairs = int(n * (S / 2 * (n / spec["n"]) + 1))
+    ej.reserve(n + nq, d)
+    expect_pairs = int(n * (S / 2 * (n / spec["n"]) + 1)) if args.mode != "join" else int(nq * S * (n / spec["n"]) * 2)
     capacity = int(expect_pairs * 1.5) + (1 << 20)
-    if args.mode == "pairs":
+    if args.mode == "join":
+        Qd = torch.from_numpy(np.ascontiguousarray(X[n:]).view(np.int16)).to("cuda:0")
+        pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
+        dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
+        npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        step = lambda: ej.join_pairs(Xd, Qd, eps, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
+    elif args.mode == "pairs":
         pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
         dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
         npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
@@ -111,14 +120,15 @@ def main():
     found = int(npairs.cpu()[0])
     ms_per_step = dt / args.steps * 1e3
     dk = (d + 63) // 64 * 64
-    tiles = pkg.tiles_evaluated(n)
+    tiles = pkg.tiles_evaluated(n) if args.mode != "join" else pkg.tiles_evaluated2(n, nq)
+    derived_flop = 2.0 * n * n * d if args.mode != "join" else 2.0 * n * nq * d
     flop_exec = 2.0 * 256 * 256 * dk * tiles
     jm = sum(join_ms) / len(join_ms)
     achieved = flop_exec / (jm * 1e-3) / 1e12
     emitted = found + (0 if args.mode == "pairs" else 0)
     out = {
-        "metric": "self-join distance TFLOPS (2*n^2*d / t)",
-        "value": 2.0 * n * n * d / (ms_per_step * 1e-3) / 1e12,
+        "metric": "self-join distance TFLOPS (2*n^2*d / t)" if args.mode != "join" else "two-set join distance TFLOPS (2*np*nq*d / t)",
+        "value": derived_flop / (ms_per_step * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -134,14 +144,16 @@ def main():
                    "n": n, "d": d, "selectivity_target": S, "eps": eps, "mode": args.mode},
         "pairs_found": found,
         "pairs_per_s": emitted / (ms_per_step * 1e-3),
-        "achieved_selectivity": (2.0 * (found - n) / n) if args.mode == "pairs" else 2.0 * found / n,
+        "achieved_selectivity": (2.0 * (found - n) / n) if args.mode == "pairs" else (2.0 * found / n if args.mode == "count" else found / max(nq, 1)),
         "kernel_ms": {"norms": sum(norm_ms) / len(norm_ms), "join": jm, "join_min": min(join_ms)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w, S, args.mode)) if args.n is None else None, "kernel": "k_join", "flop_per_launch": flop_exec, "tiles": tiles},
     }
-    if not args.no_cpu_baseline:
+    if args.mode == "join":
+        out["config"]["queries"] = nq
+    if not args.no_cpu_baseline and args.mode != "join":
         rows = args.cpu_rows or max(8, int(2.0e12 / (n * d * 16)))  # ~10-30 s of host work
-        out["cpu_baseline"] = cpu_baseline(X, w, eps, rows)
+        out["cpu_baseline"] = cpu_baseline(X[:n], w, eps, rows)
     print(json.dumps(out))
 
 
