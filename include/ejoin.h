@@ -68,6 +68,19 @@ const char* ejoin_strerror(int code);
 /* Text of the last HIP error seen by this context ("" if none). */
 const char* ejoin_last_hip_error(const ejoin_ctx* ctx);
 
+/* Ingestion: converts FP32 rows to the FP16 layout the joins take.  X32 (device, n rows of d floats,
+ * row stride ld32 >= d elements) -> X16 (device, 128-byte aligned, row stride ld16: a multiple of 64,
+ * >= roundup(d,64)):
+ *     X16[i][k] = fp16( scale * (X32[i][k] - center[k]) ),   k < d,
+ * every operation rounded to nearest even in FP32 before the final rounding to FP16; columns
+ * d .. ld16-1 are set to zero (the zero padding of Section 4.2).  `center` (device, d floats) may be
+ * NULL (no shift).  A shift leaves distances unchanged and a scale multiplies them by `scale` (so
+ * epsilon must be scaled too); together they move the data into the part of the FP16 range where
+ * its spacing is fine -- the remedy the paper suggests for data that converts badly (Section 5).
+ * Values that overflow FP16 become Inf and make the join report status EJOIN_STATUS_NONFINITE. */
+int ejoin_convert_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, const float* center, float scale,
+                      uint16_t* X16, int64_t ld16, void* stream);
+
 /* Step 1 of Section 3.1: s[i] = sum_k x_ik^2 for i < n, FP32, written to the device array s (n floats).
  * Accumulated on the matrix cores in the same order as the Gram products of the join. */
 int ejoin_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, void* stream);

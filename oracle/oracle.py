@@ -102,6 +102,18 @@ def decode(X: np.ndarray, d: int | None = None) -> np.ndarray:
     return P
 
 
+def convert_f32(X32: np.ndarray, scale=1.0, center=None, ld16: int | None = None) -> np.ndarray:
+    """Ingestion as its definition states it: fp16_rne(fl32(scale * fl32(x - center))), zero padded; uint16 bits."""
+    X32 = np.asarray(X32, dtype=np.float32)
+    n, d = X32.shape
+    ld16 = (d + 63) // 64 * 64 if ld16 is None else ld16
+    out = np.zeros((n, ld16), dtype=np.float16)
+    t = X32 if center is None else X32 - np.asarray(center, dtype=np.float32)[None, :]
+    with np.errstate(over="ignore"):
+        out[:, :d] = (t * np.float32(scale)).astype(np.float16)
+    return out.view(np.uint16)
+
+
 def eps2_of(eps) -> float:
     """Threshold on squared distances: the FP32 epsilon squared in FP64."""
     e = float(np.float32(eps))

@@ -52,6 +52,8 @@ def load_library() -> C.CDLL:
     lib.ejoin_join_count.argtypes = [vp, vp, i64, i64, vp, i64, i64, i32, f32, vp, vp, vp, vp]
     lib.ejoin_tiles_evaluated2.restype = i64
     lib.ejoin_tiles_evaluated2.argtypes = [i64, i64]
+    lib.ejoin_convert_f32.restype = C.c_int
+    lib.ejoin_convert_f32.argtypes = [vp, vp, i64, i32, i64, vp, f32, vp, i64, vp]
     lib.ejoin_dist2_tile.restype = C.c_int
     lib.ejoin_dist2_tile.argtypes = [vp, vp, i64, i32, i64, i64, i64, i32, i32, vp, vp]
     lib.ejoin_status.restype = C.c_int
@@ -119,6 +121,22 @@ class EJoin:
 
     def reserve(self, n: int, d: int):
         self._check(self._lib.ejoin_reserve(self._h, int(n), int(d)), self._h)
+
+    def convert_f32(self, X32: torch.Tensor, scale: float = 1.0, center: torch.Tensor | None = None) -> torch.Tensor:
+        """FP32 (n, d) device tensor -> FP16 (n, roundup(d, 64)) device tensor: fp16(scale * (x - center)), zero padded."""
+        if X32.dtype != torch.float32 or X32.dim() != 2 or not X32.is_cuda or X32.stride(1) != 1:
+            raise EJoinError("X32 must be a 2-D float32 device tensor with contiguous rows")
+        n, d = X32.shape
+        cptr = None
+        if center is not None:
+            if center.dtype != torch.float32 or center.numel() != d or not center.is_cuda or not center.is_contiguous():
+                raise EJoinError("center must be a contiguous float32 device tensor of d elements")
+            cptr = center.data_ptr()
+        ld16 = (d + 63) // 64 * 64
+        out = torch.empty((n, ld16), dtype=torch.float16, device=X32.device)
+        self._check(self._lib.ejoin_convert_f32(self._h, X32.data_ptr(), n, d, X32.stride(0), cptr, float(scale), out.data_ptr(), ld16,
+                                                self._stream()), self._h)
+        return out
 
     def norms(self, X: torch.Tensor, d: int | None = None) -> torch.Tensor:
         n, d, ld = self._x(X, d)

@@ -204,6 +204,30 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
 
 __device__ __forceinline__ half8 as_half8(uint4 v) { return __builtin_bit_cast(half8, v); }
 
+// Ingestion: FP32 rows -> FP16 rows in the layout the join expects (row stride ld16, a multiple of 64,
+// columns d .. ld16-1 zero).  y = fp16_rne(fl32(scale * fl32(x - center_k))).  One thread per 8 output columns.
+__global__ void k_convert_f32(const float* __restrict__ X32, int64_t n, int32_t d, int64_t ld32, const float* __restrict__ center,
+                              float scale, uint16_t* __restrict__ X16, int64_t ld16) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_row = ld16 / 8;
+  if (t >= n * per_row) return;
+  const int64_t i = t / per_row;
+  const int k0 = (int)(t - i * per_row) * 8;
+  half8 h;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float p = 0.f;
+    if (k0 + k < d) {
+      float t = X32[i * ld32 + k0 + k] - (center ? center[k0 + k] : 0.f);
+      asm volatile("" : "+v"(t));  // keep the FP32 rounding of every step: no fused subtract-multiply-convert
+      p = scale * t;
+    }
+    asm volatile("" : "+v"(p));
+    h[k] = (_Float16)p;
+  }
+  *reinterpret_cast<half8*>(X16 + i * ld16 + k0) = h;
+}
+
 // Packed copy of X for the join kernel.  Xp is cut into k-blocks of 32 coordinates; block kb holds,
 // for every row r < npad, the row's four 16-byte chunks of that block, already permuted the way
 // the LDS wants them (chunk c at position c ^ swz(r)); rows n .. npad-1 are zero.  In this layout a
@@ -1005,6 +1029,22 @@ int ejoin_join_count(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp,
   if (!guard.ok) return EJOIN_EHIP;
   return run_join<true>(ctx, P, np, ldp, Q, nq, ldq, d, eps, nullptr, nullptr, 0, nullptr, counts_p, counts_q, total,
                         static_cast<hipStream_t>(stream));
+}
+
+int ejoin_convert_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, const float* center, float scale,
+                      uint16_t* X16, int64_t ld16, void* stream) {
+  if (!ctx || !X32 || !X16) return EJOIN_EINVAL;
+  if (n < 1 || n >= (int64_t)0xFFFFFFFFll - TILE || d < 1 || d > 65536) return EJOIN_EINVAL;
+  if (ld32 < d || ld16 < pad_dims(d) || (ld16 % KPAD) != 0 || !isfinite(scale)) return EJOIN_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(X16) & 127) != 0) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  const int64_t threads = n * (ld16 / 8);
+  if ((threads + 255) / 256 > 0x7FFFFFFFll) return EJOIN_EUNSUPPORTED;
+  hipLaunchKernelGGL(k_convert_f32, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream), X32, n, d,
+                     ld32, center, scale, X16, ld16);
+  EJ_TRY(hipGetLastError());
+  return EJOIN_OK;
 }
 
 int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, int64_t i0, int64_t j0, int32_t rows,

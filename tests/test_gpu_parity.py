@@ -269,3 +269,44 @@ def test_count_mode_on_dense_output(ej):
     ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
     st = parity.check_pair_sets(P, eps, pairs, None, ora_pairs, ora_d2)
     assert abs(int(ot) - ns.shape[0]) <= st["only_gpu"] + st["only_oracle"]
+
+
+def test_convert_f32_matches_the_oracle_bit_for_bit(ej):
+    rng = np.random.default_rng(41)
+    for n, d, scale, centred in [(1000, 100, 1.0, False), (333, 960, 0.01, True), (5, 64, 7.5, True), (2, 1, 1.0, False)]:
+        X32 = (rng.standard_normal((n, d)) * 40).astype(np.float32)
+        X32.flat[::97] = 1e6  # overflows FP16 unless scaled down -> Inf on both sides
+        c = (rng.standard_normal(d) * 10).astype(np.float32) if centred else None
+        got = ej.convert_f32(torch.from_numpy(X32).cuda(), scale, None if c is None else torch.from_numpy(c).cuda())
+        want = orc.convert_f32(X32, scale, c)
+        got = got.cpu().numpy().view(np.uint16)
+        assert got.shape == want.shape and np.array_equal(got, want)
+    # the converted array feeds the join directly
+    X32 = rng.random((600, 100), dtype=np.float32)
+    Xd = ej.convert_f32(torch.from_numpy(X32).cuda())
+    P = orc.decode(orc.convert_f32(X32), d=100)
+    eps = orc.select_eps_all_pairs(P, 10)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    pairs, d2, found = run_pairs(ej, Xd, eps, capacity=20000, d=100)
+    parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+
+
+def test_centring_and_scaling_recover_accuracy_on_offset_data(ej):
+    """Data far from the origin converts badly to FP16 (Section 5): shifted and scaled ingestion brings the
+    result set back to that of the FP64 join on the original FP32 data (overlap accuracy, Eq. 3)."""
+    rng = np.random.default_rng(43)
+    n, d = 1500, 64
+    X32 = (100.0 + rng.random((n, d))).astype(np.float32)  # spacing of FP16 near 100 is 1/16
+    truth = X32.astype(np.float64)
+    eps = orc.select_eps_all_pairs(truth, 32)
+    want = orc.selfjoin_pairs(truth, eps)[0]
+    Xg = torch.from_numpy(X32).cuda()
+    c = torch.from_numpy(X32.mean(axis=0).astype(np.float32)).cuda()
+    acc = {}
+    for name, scale, centre in [("raw", 1.0, None), ("centred", 1.0, c), ("centred_scaled", 4.0, c)]:
+        Xd = ej.convert_f32(Xg, scale, centre)
+        pairs, _, found = run_pairs(ej, Xd, eps * scale, capacity=400000, d=d)
+        assert found <= 400000
+        acc[name] = orc.overlap_accuracy(n, want, pairs)
+    assert acc["raw"] < 0.9
+    assert acc["centred"] > 0.99 and acc["centred_scaled"] >= acc["centred"] - 1e-3

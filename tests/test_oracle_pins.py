@@ -289,3 +289,40 @@ def test_two_set_join_of_a_set_with_itself_is_the_full_self_join():
     cp, cq, total = orc.join_count(P, P, eps)
     counts, t_self = orc.selfjoin_count(P, eps)
     assert total == 2 * t_self + 120 and np.array_equal(cp, counts + 1) and np.array_equal(cq, cp)
+
+
+# ------------------------------------------------------------------ ingestion
+def _f32(v):
+    return struct.unpack("<f", struct.pack("<f", v))[0]  # Python double -> nearest-even FP32
+
+
+def _f16_bits(v):
+    try:
+        return struct.unpack("<H", struct.pack("<e", v))[0]  # struct rounds to nearest even
+    except OverflowError:
+        return 0x7C00 if v > 0 else 0xFC00
+
+
+def test_convert_f32_rounds_to_nearest_even_like_an_independent_encoder():
+    rng = np.random.default_rng(31)
+    x = np.concatenate([rng.standard_normal(4000).astype(np.float32) * np.float32(3.0),
+                        np.array([0.0, -0.0, 1.0, 65504.0, 65519.9, 65520.0, 1e-8, 5.96e-8, 2.98e-8, 2.0**-24 * 1.5,
+                                  1.0009765625, 1.00048828125, 1.00146484375], dtype=np.float32)])
+    scale = np.float32(0.7)
+    got = orc.convert_f32(x.reshape(1, -1), scale)[0, :x.size]
+    # products of two FP32 numbers are exact in double, so each stage below rounds exactly once
+    want = [_f16_bits(_f32(float(v) * float(scale))) for v in x.tolist()]
+    assert got.tolist() == want
+    # with a shift: x - c is exact in double for these magnitudes, then rounded to FP32, then scaled
+    c = (rng.standard_normal(x.size) * 2).astype(np.float32)
+    X2 = np.stack([x, x[::-1]])
+    got = orc.convert_f32(X2, scale, center=c)[:, :x.size]
+    for r in range(2):
+        want = [_f16_bits(_f32(_f32(float(v) - float(cc)) * float(scale))) for v, cc in zip(X2[r].tolist(), c.tolist())]
+        assert got[r].tolist() == want
+    # ties go to even: 1 + 2^-11 (half-way between 1 and 1 + 2^-10) -> 1 ; 1 + 3*2^-11 -> 1 + 2^-9
+    t = orc.convert_f32(np.array([[1.00048828125, 1.00146484375]], dtype=np.float32), 1.0)[0, :2]
+    assert t.tolist() == [0x3C00, 0x3C02]
+    # padding columns are zero, the layout is (n, roundup(d, 64))
+    p = orc.convert_f32(np.ones((3, 70), dtype=np.float32))
+    assert p.shape == (3, 128) and np.all(p[:, 70:] == 0) and np.all(p[:, :70] == 0x3C00)
