@@ -61,6 +61,8 @@ def main():
                     help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points")
     ap.add_argument("--queries", type=int, default=100_000, help="query points of --mode join (same distribution, rows n .. n+queries-1)")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
+    ap.add_argument("--eps", type=float, default=None, help="override epsilon (0 = output-free run: isolates Gram + threshold from compaction)")
+    ap.add_argument("--e2e", action="store_true", help="also time one end-to-end response: pinned host X -> HBM, step, found pairs -> pinned host")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None)
     args = ap.parse_args()
@@ -79,7 +81,7 @@ def main():
     S = args.selectivity or spec["selectivity"][0]
     n = args.n or spec["n"]
     d = spec["d"]
-    eps = load_eps(w, S)
+    eps = load_eps(w, S) if args.eps is None else args.eps
     nq = args.queries if args.mode == "join" else 0
     X = datagen.generate(w, n=n + nq)
     Xd = torch.from_numpy(X[:n].view(np.int16)).to("cuda:0")
@@ -118,6 +120,28 @@ def main():
     dt = time.perf_counter() - t0
     ej.set_profiling(False)
     found = int(npairs.cpu()[0])
+    e2e = None
+    if args.e2e and args.mode == "pairs":
+        # End-to-end response time in the paper's sense (Section 4.1.1: transfers and result storage included).
+        Xh = torch.from_numpy(X[:n].view(np.int16)).pin_memory()
+        m = min(found, capacity)
+        ph = torch.empty((m, 2), dtype=torch.int32).pin_memory()
+        dh = torch.empty(m, dtype=torch.float32).pin_memory()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        Xd.copy_(Xh, non_blocking=True)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        m2 = min(int(npairs.cpu()[0]), m)
+        ph[:m2].copy_(pairs[:m2], non_blocking=True)
+        dh[:m2].copy_(dist2[:m2], non_blocking=True)
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        e2e = {"h2d_ms": (t2 - t1) * 1e3, "step_ms": (t3 - t2) * 1e3, "d2h_ms": (t4 - t3) * 1e3, "total_ms": (t4 - t1) * 1e3,
+               "h2d_bytes": Xh.numel() * 2, "d2h_bytes": m2 * 12}
     ms_per_step = dt / args.steps * 1e3
     dk = (d + 63) // 64 * 64
     tiles = pkg.tiles_evaluated(n) if args.mode != "join" else pkg.tiles_evaluated2(n, nq)
@@ -145,12 +169,15 @@ def main():
         "pairs_found": found,
         "pairs_per_s": emitted / (ms_per_step * 1e-3),
         "achieved_selectivity": (2.0 * (found - n) / n) if args.mode == "pairs" else (2.0 * found / n if args.mode == "count" else found / max(nq, 1)),
-        "kernel_ms": {"norms": sum(norm_ms) / len(norm_ms), "join": jm, "join_min": min(join_ms)},
+        "kernel_ms": {"norms": sum(norm_ms) / len(norm_ms), "join": jm, "join_min": min(join_ms), "join_median": sorted(join_ms)[len(join_ms) // 2]},
+        "pairs_write_GBps": (min(found, capacity) * 12 / (jm * 1e-3) / 1e9) if args.mode != "count" else 0.0,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w, S, args.mode)) if args.n is None else None, "kernel": "k_join", "flop_per_launch": flop_exec, "tiles": tiles},
     }
     if args.mode == "join":
         out["config"]["queries"] = nq
+    if e2e is not None:
+        out["end_to_end"] = e2e
     if not args.no_cpu_baseline and args.mode != "join":
         rows = args.cpu_rows or max(8, int(2.0e12 / (n * d * 16)))  # ~10-30 s of host work
         out["cpu_baseline"] = cpu_baseline(X[:n], w, eps, rows)
