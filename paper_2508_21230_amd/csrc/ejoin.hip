@@ -401,7 +401,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const int wm = wave >> 2, wn = wave & 3;
   const int r32 = lane & 31, hi = lane >> 5;
   const int nsl = a.nslices;       // data slices per tile
-  const int nslT = nsl + 1;        // plus the augmentation slice (nslT >= 3)
+  const int nslT = nsl + 1;        // plus the augmentation slice (nslT >= DIST: nsl >= 2 because d is padded to 64)
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
   // --- global->LDS copies.  One global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 B) = 16 rows of a
@@ -518,6 +518,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   int iks = 0;
   bool issue_live = true;       // the issue cursor still points at real work
   bool issue_on_next = false;   // ... of the tile after the one being computed
+  bool issue_pending = false;   // ... and has finished that one too (see issue_one)
   const char* pa = XbA + (int64_t)I * (TILE * 64);
   const char* pb = XbB + (int64_t)J * (TILE * 64);
   const uint32_t lds_w = lds0 + wave * 1024;
@@ -532,11 +533,19 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     pb += kstrideB;
     if (++iks == nslT) {
       iks = 0;
-      const bool to_next = issue_live && !issue_on_next && have_next;
-      issue_live = to_next;
-      issue_on_next = to_next;
-      pa = XbA + (int64_t)(to_next ? In : 0) * (TILE * 64);
-      pb = XbB + (int64_t)(to_next ? Jn : 0) * (TILE * 64);
+      if (issue_live && issue_on_next) {
+        // The cursor has finished the tile AFTER the one being computed.  That happens only when a tile
+        // has exactly DIST slices (d <= 64), and then with the last issue of the current tile; which
+        // tile comes two ahead is decided at the end of this tile, where the cursor is set on it.
+        issue_pending = true;
+        issue_live = false;
+      } else {
+        const bool to_next = issue_live && have_next;
+        issue_live = to_next;
+        issue_on_next = to_next;
+        pa = XbA + (int64_t)(to_next ? In : 0) * (TILE * 64);
+        pb = XbB + (int64_t)(to_next ? Jn : 0) * (TILE * 64);
+      }
     }
   };
   for (int q = 0; q < DIST; ++q) issue_one(q);
@@ -682,6 +691,13 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       }
       have_next = tc.next(In, Jn);
       issue_on_next = false;  // the issue cursor, if it had moved on, is now on the current tile
+      if (issue_pending) {    // ... or already past it: put it on the tile just chosen
+        issue_pending = false;
+        issue_live = have_next;
+        issue_on_next = have_next;
+        pa = XbA + (int64_t)(have_next ? In : 0) * (TILE * 64);
+        pb = XbB + (int64_t)(have_next ? Jn : 0) * (TILE * 64);
+      }
     }
   }
   xcd_leave();

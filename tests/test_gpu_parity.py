@@ -141,6 +141,27 @@ def test_edge_sizes(ej, n, d):
     parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
 
 
+@pytest.mark.parametrize("n,d", [(6500, 64), (7000, 40), (6200, 128), (5900, 192)])
+def test_more_tiles_than_workgroups_at_small_d(ej, n, d):
+    """Every workgroup walks several tiles (351 .. 406 tiles on 256 workgroups).  At d <= 64 a tile has as many
+    slices as the copy pipeline runs ahead, so the copy cursor finishes the tile after the current one before the
+    tile after that is known."""
+    print(f"multi-tile n={n} d={d}", flush=True)
+    rng = np.random.default_rng(n + d)
+    X = rng.random((n, d), dtype=np.float32).astype(np.float16).view(np.uint16)
+    P = orc.decode(X)
+    eps = orc.select_eps_sample(P[np.sort(rng.choice(n, size=1500, replace=False))], 8, n)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    ld = (d + 63) // 64 * 64
+    pairs, d2, found = run_pairs(ej, dev(pad(X, ld)), eps, capacity=ora_pairs.shape[0] * 2 + 1024, d=d)
+    assert found == pairs.shape[0]
+    parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+    # count mode walks the same schedule
+    counts, total = ej.selfjoin_count(dev(pad(X, ld)), eps, d=d)
+    torch.cuda.synchronize()
+    assert int(total.cpu()[0]) == found - n
+
+
 def test_unpadded_d_with_zero_columns(ej):
     # d = 100 stored with ld = 128 and zero padding (the paper pads d to a multiple of 64 with zeros)
     rng = np.random.default_rng(5)

@@ -72,6 +72,23 @@ def test_two_set_pairs_against_oracle(ej, w, n_p, n_q, S):
     assert none is None and int(total2.cpu()[0]) == found and torch.equal(cp2, cp)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_two_set_more_tiles_than_workgroups(ej, d):
+    # 17 x 18 = 306 tiles on 256 workgroups; at d = 64 a tile has exactly as many slices as the copies run ahead
+    rng = np.random.default_rng(900 + d)
+    n_p, n_q = 4200, 4400
+    XP = rng.random((n_p, d), dtype=np.float32).astype(np.float16).view(np.uint16)
+    XQ = rng.random((n_q, d), dtype=np.float32).astype(np.float16).view(np.uint16)
+    P, Q = orc.decode(XP), orc.decode(XQ)
+    eps = orc.eps_for_pair_rank(orc.dist2_block2(P, Q, 0, 1200, 0, 1200).ravel(), 3000)
+    op, od2 = orc.join_pairs(P, Q, eps)
+    pairs, d2, npairs = ej.join_pairs(dev(XP), dev(XQ), float(eps), capacity=op.shape[0] * 2 + 4096)
+    torch.cuda.synchronize()
+    gp, gd2, found = parity.to_host_pairs(pairs, d2, npairs)
+    assert found == gp.shape[0]
+    print("  ", check_two_set(P, Q, eps, gp, gd2, op, od2), flush=True)
+
+
 def test_two_set_join_of_a_set_with_itself_matches_the_self_join(ej):
     X = datagen.generate(2, n=2000)
     P = orc.decode(X)
