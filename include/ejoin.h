@@ -25,8 +25,11 @@
  *         acc' = a_ij - s_i/2 - s_j/2,    d2 = max(0, -2 acc'),    pass  <=>  acc' >= -fl(eps * eps) / 2,
  *     where a_ij and s_i are accumulated over k in ascending order on the matrix cores in steps
  *     of 16 coordinates, and the two norm terms are added by one more matrix-core step (Step 3 of
- *     Section 3.1 folded into the accumulation).  d2(i, i) == 0 and duplicates of a point are at
- *     distance 0 exactly.  "<= epsilon" is the paper's comparison (Section 2.2.1).
+ *     Section 3.1 folded into the accumulation).  The self pair (i, i) is always reported, with
+ *     d2 = 0.  Duplicates of a point are at distance exactly 0 whenever the point's s_i is at least
+ *     max(2^-16 s_max, 2^-14), s_max the largest s of the data (the norm term is then carried exactly;
+ *     below that it is carried to about 2^-41 s_max).  "<= epsilon" is the paper's comparison
+ *     (Section 2.2.1).
  *   - Data range: every s_i = sum_k x_ik^2 must be finite and below 2^31 (the paper's method
  *     assumes data commensurate with the FP16 range, Section 4.5).  This is detected on the
  *     device: a join over data outside the range reports zero pairs / zero counts and

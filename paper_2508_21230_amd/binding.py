@@ -94,7 +94,11 @@ class EJoin:
             self._lib.ejoin_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the modules this needs may already be gone
+            pass
 
     def _check(self, rc: int, h):
         if rc != EJOIN_OK:

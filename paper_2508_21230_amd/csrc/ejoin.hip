@@ -144,17 +144,23 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   }
 }
 
-// Rows past the end of the data set use this augmentation row: -60000 in place of -s/2, so that
-// none of their pairs passes the filter for any ordinary epsilon (the rare path masks them exactly)
-// and nothing non-finite enters the matrix cores.
-__device__ __forceinline__ uint4 aux_row_out_of_range() { return make_uint4(0xFB53u /* -60000 in FP16 */, 0u, 0x3C003C00u, 0x3C00u); }
+// Rows past the end of the data set use this augmentation row: -60000 c in place of -s/2 (at least
+// the largest norm of the data), so that none of their pairs passes the filter for any ordinary
+// epsilon (the rare path masks them exactly) and nothing non-finite enters the matrix cores.
+__device__ __forceinline__ uint4 aux_row_out_of_range(uint32_t cbits) {
+  return make_uint4(0xFB53u /* -60000 in FP16 */, 0u, cbits | (cbits << 16), cbits);
+}
 
 // Augmentation rows.  Step 3 of Section 3.1 (dist^2 = s_i + s_j - 2 a_ij) is folded into the
 // matrix-core accumulation: after the d/16 Gram steps one more 16-wide MFMA step adds
 // -s_i/2 - s_j/2 to a_ij, so the accumulator ends as acc' = -dist^2 / 2 and the filter becomes a
-// sign-like test against -eps^2/2.  -s/2 is FP32; it is split exactly into three FP16 pieces
-// p1 + p2 + p3 (scaled by 2^-m so that p1 fits FP16; m = 0 whenever max s < 65536).  Point i's
-// 16-byte row is  H_i = { p1, p2, p3, 0, c, c, c, 0 }  with c = 2^m.  As the A operand of the extra
+// sign-like test against -eps^2/2.  -s/2 is FP32; scaled by 2^-m it is split into three FP16 pieces
+// p1 + p2 + p3, where m puts the largest norm of the data just below 2^16 (s_max / 2 < 2^15 2^m),
+// within -14 <= m <= 15 so that c = 2^m is a normal FP16 value (the matrix cores align the products
+// of a step by their exponent fields; a subnormal c would cost them low bits).  The split is exact
+// for every point with s >= max(2^-16 s_max, 2^-14): the 24 mantissa bits of s / 2^(m+1) then lie
+// above FP16's smallest subnormal.  A smaller norm is carried to 2^-25 2^m absolute.  Point i's
+// 16-byte row is  H_i = { p1, p2, p3, 0, c, c, c, 0 }.  As the A operand of the extra
 // step a row is used as is (k = 0..7; k = 8..15 are zero), as the B operand its two halves are
 // swapped, { c, c, c, 0, q1, q2, q3, 0 }, so that  A_i . B_j = c (p1+p2+p3)_i + c (q1+q2+q3)_j
 // = -s_i/2 - s_j/2  (every product is exact in FP32).
@@ -171,21 +177,21 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
   if (mb >= 0x7f800000u) st = ST_NONFINITE;  // Inf or NaN among the norms
   else {
     const int e = (int)(mb >> 23) - 127;  // max s < 2^(e+1)
-    m = e > 15 ? e - 15 : 0;
+    m = e - 15 < -14 ? -14 : e - 15;
     if (m > 15) st = ST_NORM_RANGE;  // 2^m must be an FP16 value: needs max s < 2^31
   }
+  const _Float16 c = (_Float16)ldexpf(1.f, m > 15 ? 15 : m);
+  auto bits = [](_Float16 x) { return (uint32_t)__builtin_bit_cast(uint16_t, x); };
   if (i == 0) status_and_max[0] = st;
   if (i >= npad) return;
   uint4 h = make_uint4(0, 0, 0, 0);
-  if (i >= n) h = aux_row_out_of_range();
+  if (i >= n) h = aux_row_out_of_range(bits(c));
   else if (st == ST_OK) {
     const float v = ldexpf(-0.5f * s[i], -m);
     const _Float16 p1 = (_Float16)v;
     const float r1 = v - (float)p1;
     const _Float16 p2 = (_Float16)r1;
     const _Float16 p3 = (_Float16)(r1 - (float)p2);
-    const _Float16 c = (_Float16)ldexpf(1.f, m);
-    auto bits = [](_Float16 x) { return (uint32_t)__builtin_bit_cast(uint16_t, x); };
     h.x = bits(p1) | (bits(p2) << 16);
     h.y = bits(p3);
     h.z = bits(c) | (bits(c) << 16);
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int rr = bi + 8 * (r >> 2) + 4 * hi + (r & 3);
-      if (rr < rows) out[(int64_t)rr * cols + c] = fmaxf(-2.f * acc[r], 0.f);
+      if (rr < rows) out[(int64_t)rr * cols + c] = (i0 + rr == j0 + c) ? 0.f : fmaxf(-2.f * acc[r], 0.f);
     }
   }
 }
@@ -495,6 +501,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     dirty = true;
   };
 
+  // 32 x 32 blocks of this wave's tile that the diagonal of a diagonal tile crosses (bit mt*2 + nt)
+  uint32_t diag_blocks = 0;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int mt = 2 * wn + nt - 4 * wm;
+    if (mt >= 0 && mt < 4) diag_blocks |= 1u << (mt * 2 + nt);
+  }
+
   // ---------------- prologue
   TileCursor tc;
   tc.init(blockIdx.x, gridDim.x, a);
@@ -625,6 +639,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         }
       }
       if (skip) blocks_hit = 0;
+      else if (diag && !COUNT) blocks_hit |= diag_blocks;  // self pairs are emitted whatever the arithmetic says
       // rare path, one block at a time
       while (blocks_hit) {
         const int b = __builtin_ctz(blocks_hit);
@@ -646,11 +661,12 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          if (__ballot(v[r] >= a.thr) == 0) continue;  // most registers of a flagged block hold no hit
           const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
+          const bool selfp = !COUNT && diag && i == j && i < nnA;  // (i, i) belongs to the result by definition
+          if (__ballot(v[r] >= a.thr || selfp) == 0) continue;  // most registers of a flagged block hold no hit
           // rows/columns past n carry a large negative marker, which a huge epsilon can still reach: mask them here
           bool pass = v[r] >= a.thr && i < nnA && j < nnB;
-          if (diag) pass = pass && (COUNT ? i < j : i <= j);
+          if (diag) pass = (pass && i < j) || selfp;
           const unsigned long long mask = __ballot(pass);
           if (mask) {
             const uint32_t cnt = __popcll(mask);
@@ -669,7 +685,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
                 const uint32_t e = fill + rank;
                 stg[3 * e] = i;
                 stg[3 * e + 1] = j;
-                stg[3 * e + 2] = __float_as_uint(fmaxf(-2.f * v[r], 0.f));
+                stg[3 * e + 2] = selfp ? 0u : __float_as_uint(fmaxf(-2.f * v[r], 0.f));
               }
               fill += cnt;
             }

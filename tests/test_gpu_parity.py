@@ -162,6 +162,52 @@ def test_more_tiles_than_workgroups_at_small_d(ej, n, d):
     assert int(total.cpu()[0]) == found - n
 
 
+@pytest.mark.parametrize("n,d", [(700, 2048), (300, 4096), (900, 1), (900, 33)])
+def test_extreme_dimensionalities(ej, n, d):
+    print(f"extreme d: n={n} d={d}", flush=True)
+    rng = np.random.default_rng(17 * d + n)
+    X = rng.random((n, d), dtype=np.float32).astype(np.float16).view(np.uint16)
+    P = orc.decode(X)
+    eps = orc.select_eps_all_pairs(P, 12)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    ld = (d + 63) // 64 * 64
+    pairs, d2, found = run_pairs(ej, dev(pad(X, ld)), eps, capacity=ora_pairs.shape[0] * 2 + 1024, d=d)
+    assert found == pairs.shape[0]
+    parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+
+
+@pytest.mark.parametrize("kind", ["small", "mixed", "tiny_among_large"])
+def test_small_and_mixed_norms(ej, kind):
+    """The norm term of the expansion is carried as three FP16 pieces scaled to the largest norm of the data:
+    data of small norm, and points of very different norms in one set, must meet the same parity bar."""
+    rng = np.random.default_rng({"small": 1, "mixed": 2, "tiny_among_large": 3}[kind])
+    n, d = 1200, 128
+    X32 = rng.random((n, d), dtype=np.float32)
+    if kind == "small":
+        X32 *= np.float32(0.01)                       # s ~ 4e-3
+    elif kind == "mixed":
+        X32 *= (10.0 ** rng.uniform(-2.5, 0.5, size=(n, 1))).astype(np.float32)   # s from ~4e-4 to ~4e2
+    else:
+        X32[: n // 2] *= np.float32(2.0 ** -11)       # s ~ 1e-5 next to s ~ 40: ratio above 2^16
+        X32[n // 2:] *= np.float32(1.0)
+    X = X32.astype(np.float16).view(np.uint16)
+    X[7] = X[3]                                        # an exact duplicate among the first (small-norm) points
+    P = orc.decode(X)
+    eps = orc.select_eps_all_pairs(P, 10)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    pairs, d2, found = run_pairs(ej, dev(X), eps, capacity=ora_pairs.shape[0] * 2 + 1024)
+    parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
+    # epsilon = 0: every self pair, with distance 0, whatever the norms; the duplicate too where the norm term is exact
+    pairs0, d20, found0 = run_pairs(ej, dev(X), 0.0, capacity=4 * n)
+    keys = set(map(tuple, pairs0.tolist()))
+    assert all((i, i) in keys for i in range(n))
+    assert np.all(d20[pairs0[:, 0] == pairs0[:, 1]] == 0.0)
+    if kind != "tiny_among_large":
+        assert (3, 7) in keys and found0 == n + 1
+    D = ej.dist2_tile(dev(X), 0, 0, 64, 64).cpu().numpy()
+    assert np.all(np.diag(D) == 0.0)
+
+
 def test_unpadded_d_with_zero_columns(ej):
     # d = 100 stored with ld = 128 and zero padding (the paper pads d to a multiple of 64 with zeros)
     rng = np.random.default_rng(5)
