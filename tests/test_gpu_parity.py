@@ -65,7 +65,7 @@ def test_dist2_tile_against_oracle(ej, workload, n, i0, j0, rows, cols):
     got = ej.dist2_tile(dev(X), i0, j0, rows, cols).cpu().numpy().astype(np.float64)
     want = orc.dist2_block(P, i0, rows, j0, cols)
     s = orc.norms(P)
-    tol = np.maximum(parity.REL * want, parity.FLOOR * (s[i0:i0 + rows, None] + s[None, j0:j0 + cols]))
+    tol = parity.value_tolerance(want, s[i0:i0 + rows, None] + s[None, j0:j0 + cols], s.max())
     assert np.all(np.abs(got - want) <= tol)
     if i0 == j0 and rows == cols:
         assert np.all(np.diag(got) == 0.0)  # norms are the Gram diagonal bit for bit

@@ -31,16 +31,20 @@ def check_two_set(P, Q, eps, gp, gd2, op, od2):
     assert np.all(kgs[1:] != kgs[:-1]), "duplicate pairs"
     ko = orc.pair_keys(op)
     cg, co = np.isin(kgs, ko, assume_unique=True), np.isin(ko, kgs, assume_unique=True)
-    assert orc.boundary_band(od2[~co], eps, parity.REL).all(), "missed a pair outside the boundary band"
+    sp, sq = orc.norms(P), orc.norms(Q)
+    s_max = max(sp.max(), sq.max())
+    oo = op[~co]
+    assert parity.in_band(od2[~co], eps, sp[oo[:, 0]] + sq[oo[:, 1]], s_max).all(), "missed a pair outside the boundary band"
     only_g = kgs[~cg]
     if only_g.size:
-        d2x = np.array([orc.dist2_block2(P, Q, int(k >> np.uint64(32)), 1, int(k & np.uint64(0xFFFFFFFF)), 1)[0, 0] for k in only_g])
-        assert orc.boundary_band(d2x, eps, parity.REL).all(), "extra pair outside the boundary band"
-    sp, sq = orc.norms(P), orc.norms(Q)
+        gi = (only_g >> np.uint64(32)).astype(np.int64)
+        gj = (only_g & np.uint64(0xFFFFFFFF)).astype(np.int64)
+        d2x = np.array([orc.dist2_block2(P, Q, int(i), 1, int(j), 1)[0, 0] for i, j in zip(gi, gj)])
+        assert parity.in_band(d2x, eps, sp[gi] + sq[gj], s_max).all(), "extra pair outside the boundary band"
     g = gd2[order][cg].astype(np.float64)
     o = od2[co]
     pp = op[co]
-    tol = np.maximum(parity.REL * o, parity.FLOOR * (sp[pp[:, 0]] + sq[pp[:, 1]]))
+    tol = parity.value_tolerance(o, sp[pp[:, 0]] + sq[pp[:, 1]], s_max)
     assert (np.abs(g - o) <= tol).all()
     return dict(gpu=len(kg), oracle=len(ko), only_gpu=int(only_g.size), only_oracle=int((~co).sum()))
 
