@@ -14,21 +14,23 @@ import torch
 from . import build as _build
 
 EJOIN_OK = 0
-_lib = None
+_libs: dict = {}
 
 
 class EJoinError(RuntimeError):
     pass
 
 
-def load_library() -> C.CDLL:
-    """dlopen libejoin.so (building it first only if it has never been built)."""
-    global _lib
-    if _lib is not None:
-        return _lib
-    if not os.path.exists(_build.LIB):
+def load_library(path: str | None = None) -> C.CDLL:
+    """dlopen libejoin.so (building it first only if it has never been built).
+
+    `path` names another build of the same source (the ablation variants of build.build_ablations)."""
+    key = os.path.abspath(path) if path else _build.LIB
+    if key in _libs:
+        return _libs[key]
+    if path is None and not os.path.exists(_build.LIB):
         _build.build_library()
-    lib = C.CDLL(_build.LIB)
+    lib = C.CDLL(key)
     vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float
     lib.ejoin_create.restype = C.c_int
     lib.ejoin_create.argtypes = [C.POINTER(vp), C.c_int]
@@ -64,7 +66,7 @@ def load_library() -> C.CDLL:
     lib.ejoin_last_kernel_ms.argtypes = [vp, C.POINTER(f32), C.POINTER(f32)]
     lib.ejoin_tiles_evaluated.restype = i64
     lib.ejoin_tiles_evaluated.argtypes = [i64]
-    _lib = lib
+    _libs[key] = lib
     return lib
 
 
@@ -79,10 +81,10 @@ def tiles_evaluated2(n_p: int, n_q: int) -> int:
 class EJoin:
     """One context (ejoin_ctx) on one GPU.  Methods mirror the C entry points."""
 
-    def __init__(self, device: int = 0):
+    def __init__(self, device: int = 0, lib_path: str | None = None):
         if not torch.cuda.is_available():
             raise EJoinError("no GPU visible: the epsilon self-join has no CPU path")
-        self._lib = load_library()
+        self._lib = load_library(lib_path)
         self.device = torch.device("cuda", device)
         h = C.c_void_p()
         self._check(self._lib.ejoin_create(C.byref(h), device), None)

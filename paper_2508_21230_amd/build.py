@@ -19,21 +19,45 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile csrc/ejoin.hip -> libejoin.so (always recompiles; takes a few seconds)."""
+#: ablation builds of the join kernel: name -> extra compiler defines (see the top of csrc/ejoin.hip)
+ABLATIONS = {
+    "three_stages": ["-DEJOIN_ABL_NSTAGE=3"],
+    "no_swizzle": ["-DEJOIN_ABL_NOSWIZZLE"],
+    "rowmajor_tiles": ["-DEJOIN_ABL_ROWMAJOR_TILES", "-DEJOIN_ABL_NOALIGN"],
+    "no_xcd_align": ["-DEJOIN_ABL_NOALIGN"],
+    "no_prefilter": ["-DEJOIN_ABL_NOPREFILTER"],
+}
+ABLATION_DIR = os.path.join(PKG, "ablation")
+
+
+def _compile(out: str, defines=(), verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     if not os.path.exists(hipcc):
         hipcc = "hipcc"
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", INCLUDE, "-o", tmp, SRC]
+    tmp = out + ".tmp%d" % os.getpid()
+    cmd = [hipcc, *HIPCC_FLAGS, *defines, "-I", INCLUDE, "-o", tmp, SRC]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose:
         print(" ".join(cmd))
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/ejoin.hip -> libejoin.so (always recompiles; takes a few seconds)."""
+    return _compile(LIB, verbose=verbose)
+
+
+def build_ablations(verbose: bool = False) -> dict:
+    """Compile the ablation variants -> ablation/libejoin_<name>.so (measurement only, see bench_ablation.py)."""
+    os.makedirs(ABLATION_DIR, exist_ok=True)
+    return {name: _compile(os.path.join(ABLATION_DIR, f"libejoin_{name}.so"), defs, verbose) for name, defs in ABLATIONS.items()}
 
 
 if __name__ == "__main__":
+    import sys
     print(build_library(verbose=True))
+    if "--ablations" in sys.argv:
+        print(build_ablations(verbose=True))

@@ -30,7 +30,14 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 constexpr int TILE = 256;     // a workgroup computes a TILE x TILE block of the distance matrix
 constexpr int KPAD = 64;      // d is processed rounded up to a multiple of KPAD (zero padded by the caller)
 constexpr int KSLICE = 32;    // coordinates per LDS stage (64 B per row)
-constexpr int NSTAGE = 4;     // ring of LDS stages; NSTAGE-1 slices are in flight from L2/HBM
+// Ablation builds (bench_ablation.py) take one design element out at a time; every variant computes the
+// same results.  EJOIN_ABL_NSTAGE=3 (one LDS stage less), EJOIN_ABL_NOSWIZZLE (plain LDS rows),
+// EJOIN_ABL_ROWMAJOR_TILES (tiles dealt round-robin in row-major order), EJOIN_ABL_NOALIGN (workgroups of
+// an XCD never re-aligned), EJOIN_ABL_NOPREFILTER (every block goes through the exact path).
+#ifndef EJOIN_ABL_NSTAGE
+#define EJOIN_ABL_NSTAGE 4
+#endif
+constexpr int NSTAGE = EJOIN_ABL_NSTAGE;  // ring of LDS stages; NSTAGE-1 slices are in flight from L2/HBM
 constexpr int DIST = NSTAGE - 1;
 constexpr int THREADS = 512;  // 8 wavefronts: 2 (rows) x 4 (columns), wave tile 128 x 64
 constexpr int SB = 16;        // tiles per super-block edge (one super-block = 256 tiles = one pass of the chip)
@@ -43,6 +50,7 @@ constexpr int STG_WAVE_BYTES = STG_CAP * 12;
 constexpr int LDS_BYTES = STG_OFF + 8 * STG_WAVE_BYTES;
 constexpr int NUM_XCD = 8;
 static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+static_assert(NSTAGE == 3 || NSTAGE == 4, "the slice pipeline reads one slice ahead: at least two slices in flight");
 
 // Device status word written by k_aux, read by the other kernels.
 constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
@@ -52,7 +60,11 @@ constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
 // ds_read_b128 serves 16 lanes per clock; 16 consecutive rows at the same logical chunk then fall
 // into 16 distinct 16-byte bank groups (4 rows per 256 B bank line x 4 positions).  This is the
 // role the XOR swizzle of Section 3.3.5 (Eq. 2) plays on the A100's 32 banks.
+#ifdef EJOIN_ABL_NOSWIZZLE
+__host__ __device__ __forceinline__ int swz(int) { return 0; }
+#else
 __host__ __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+#endif
 
 struct JoinArgs {
   // "points" (rows of the distance matrix) and "query points" (columns); the self-join passes the same set twice
@@ -310,7 +322,10 @@ struct TileCursor {
   uint64_t target;       // position of this workgroup's next tile in the XCD's list
   uint64_t rank0;        // position of the first non-empty tile of the current super-block's rectangle
   uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
+  uint32_t start, wpx_all;  // (row-major ablation only) first tile and stride of this workgroup
   __device__ void init(uint32_t block, uint32_t nblocks, const JoinArgs& a) {
+    start = block;
+    wpx_all = nblocks;
     xcd = block % NUM_XCD;
     wpx = (nblocks - xcd + NUM_XCD - 1) / NUM_XCD;  // workgroups with this XCD id
     self = a.self;
@@ -326,6 +341,26 @@ struct TileCursor {
   __device__ bool cell_ok(uint32_t I, uint32_t J) const { return self ? (I <= J && J < ntB) : (I < ntA && J < ntB); }
   // next tile of this workgroup; false when the work is exhausted
   __device__ bool next(uint32_t& I, uint32_t& J) {
+#ifdef EJOIN_ABL_ROWMAJOR_TILES
+    // tiles of the triangle (or grid) in row-major order, tile t to workgroup t % nblocks; P, Q hold the
+    // row and column of this workgroup's next tile, rank0 the stride
+    if (rank0 == 0) {  // first call
+      rank0 = (uint64_t)wpx_all;
+      P = 0;
+      Q = start;
+    } else {
+      Q += (uint32_t)rank0;
+    }
+    while (P < ntA && Q >= ntB) {
+      Q -= ntB;
+      ++P;
+      if (self) Q += P;  // row P of the triangle starts at column P
+    }
+    if (P >= ntA) return false;
+    I = __builtin_amdgcn_readfirstlane(P);
+    J = __builtin_amdgcn_readfirstlane(Q);
+    return true;
+#endif
     while (P < nsbA) {
       const uint32_t xp = (xcd + sbi) & 7;
       const uint32_t I0 = P * SB + (xp >> 2) * 8, J0 = Q * SB + (xp & 3) * 4;
@@ -564,7 +599,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   };
   for (int q = 0; q < DIST; ++q) issue_one(q);
   // slice 0 has landed when only the copies of the DIST-1 younger slices (4 per slice and wave) are outstanding
-  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 1)) : "memory");
   __syncthreads();
   half8 fa0[4], fb0[2], fa1[4], fb1[2];
   load_frags(0, offA[0], offB[0], fa0, fb0);
@@ -576,7 +611,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
     // (a) this wave's copies of slice G+1 have landed once only slice G+2's four are outstanding
     if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
-    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 2)) : "memory");
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
     // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
@@ -602,7 +637,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     // ---------------- the augmentation slice: one step, then the filter
     {
       if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
-      else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 2)) : "memory");
       wg_barrier();
       issue_one(G + DIST);
       ++G;
@@ -638,60 +673,70 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
       }
+#ifdef EJOIN_ABL_NOPREFILTER
+      blocks_hit = 0xFF;
+#endif
       if (skip) blocks_hit = 0;
       else if (diag && !COUNT) blocks_hit |= diag_blocks;  // self pairs are emitted whatever the arithmetic says
-      // rare path, one block at a time
-      while (blocks_hit) {
-        const int b = __builtin_ctz(blocks_hit);
-        blocks_hit &= blocks_hit - 1;
-        float16v v;
-        switch (b) {
-          case 0: v = acc[0][0]; break;
-          case 1: v = acc[0][1]; break;
-          case 2: v = acc[1][0]; break;
-          case 3: v = acc[1][1]; break;
-          case 4: v = acc[2][0]; break;
-          case 5: v = acc[2][1]; break;
-          case 6: v = acc[3][0]; break;
-          default: v = acc[3][1]; break;
-        }
-        const int mt = b >> 1, nt = b & 1;
-        const uint32_t nnA = (uint32_t)a.nA, nnB = (uint32_t)a.nB;
-        const uint32_t j = J * TILE + wn * 64 + nt * 32 + r32;
-        const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
+      // rare path, one block at a time.  Two instances: the common one for tiles off the diagonal, and
+      // the one for diagonal tiles of the self-join, which keeps i < j only and emits the self pairs.
+      auto exact_path = [&](auto diag_c) {
+        constexpr bool DIAG = decltype(diag_c)::value;
+        while (blocks_hit) {
+          const int b = __builtin_ctz(blocks_hit);
+          blocks_hit &= blocks_hit - 1;
+          float16v v;
+          switch (b) {
+            case 0: v = acc[0][0]; break;
+            case 1: v = acc[0][1]; break;
+            case 2: v = acc[1][0]; break;
+            case 3: v = acc[1][1]; break;
+            case 4: v = acc[2][0]; break;
+            case 5: v = acc[2][1]; break;
+            case 6: v = acc[3][0]; break;
+            default: v = acc[3][1]; break;
+          }
+          const int mt = b >> 1, nt = b & 1;
+          const uint32_t nnA = (uint32_t)a.nA, nnB = (uint32_t)a.nB;
+          const uint32_t j = J * TILE + wn * 64 + nt * 32 + r32;
+          const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
-          const bool selfp = !COUNT && diag && i == j && i < nnA;  // (i, i) belongs to the result by definition
-          if (__ballot(v[r] >= a.thr || selfp) == 0) continue;  // most registers of a flagged block hold no hit
-          // rows/columns past n carry a large negative marker, which a huge epsilon can still reach: mask them here
-          bool pass = v[r] >= a.thr && i < nnA && j < nnB;
-          if (diag) pass = (pass && i < j) || selfp;
-          const unsigned long long mask = __ballot(pass);
-          if (mask) {
-            const uint32_t cnt = __popcll(mask);
-            if (COUNT) {
-              if (pass) {
-                atomicAdd(&a.counts[i], 1u);
-                if (a.self) atomicAdd(&a.counts[j], 1u);
-                else if (a.counts_b) atomicAdd(&a.counts_b[j], 1u);
+          for (int r = 0; r < 16; ++r) {
+            const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
+            // (i, i) belongs to the result by definition, whatever the arithmetic says
+            const bool selfp = DIAG && !COUNT && i == j && i < nnA;
+            if (__ballot(v[r] >= a.thr || selfp) == 0) continue;  // most registers of a flagged block hold no hit
+            // rows/columns past n carry a large negative marker, which a huge epsilon can still reach: mask them here
+            bool pass = v[r] >= a.thr && i < nnA && j < nnB;
+            if (DIAG) pass = (pass && i < j) || selfp;
+            const unsigned long long mask = __ballot(pass);
+            if (mask) {
+              const uint32_t cnt = __popcll(mask);
+              if (COUNT) {
+                if (pass) {
+                  atomicAdd(&a.counts[i], 1u);
+                  if (a.self) atomicAdd(&a.counts[j], 1u);
+                  else if (a.counts_b) atomicAdd(&a.counts_b[j], 1u);
+                }
+                hits += cnt;
+                dirty = true;
+              } else {
+                if (fill + cnt > STG_CAP) flush();
+                const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                if (pass) {
+                  const uint32_t e = fill + rank;
+                  stg[3 * e] = i;
+                  stg[3 * e + 1] = j;
+                  stg[3 * e + 2] = selfp ? 0u : __float_as_uint(fmaxf(-2.f * v[r], 0.f));
+                }
+                fill += cnt;
               }
-              hits += cnt;
-              dirty = true;
-            } else {
-              if (fill + cnt > STG_CAP) flush();
-              const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-              if (pass) {
-                const uint32_t e = fill + rank;
-                stg[3 * e] = i;
-                stg[3 * e + 1] = j;
-                stg[3 * e + 2] = selfp ? 0u : __float_as_uint(fmaxf(-2.f * v[r], 0.f));
-              }
-              fill += cnt;
             }
           }
         }
-      }
+      };
+      if (diag) exact_path(T_{});
+      else exact_path(F_{});
     }
     // first fragments of the next tile (slice G was certified by the augmentation slice's barrier);
     // read after the filter to keep its registers free
@@ -901,6 +946,9 @@ int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const 
     // (measured on MI355X: +12..16 % over never aligning; every tile costs more than it gains)
     const int per = 512 / (a.nslices + 1);
     a.sync_mode = per < 8 ? 8 : (per > 64 ? 64 : per);
+#ifdef EJOIN_ABL_NOALIGN
+    a.sync_mode = 0;
+#endif
   }
 
   if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
