@@ -57,8 +57,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=3, help="workload id 1..5 (datagen.WORKLOADS)")
     ap.add_argument("--selectivity", type=int, default=None)
-    ap.add_argument("--mode", choices=["pairs", "count", "join"], default="pairs",
-                    help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points")
+    ap.add_argument("--mode", choices=["pairs", "count", "join", "split"], default="pairs",
+                    help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points; "
+                         "split: higher-accuracy self-join of FP32 data (the workload's points plus seeded sub-FP16 noise), pair list")
     ap.add_argument("--queries", type=int, default=100_000, help="query points of --mode join (same distribution, rows n .. n+queries-1)")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
     ap.add_argument("--eps", type=float, default=None, help="override epsilon (0 = output-free run: isolates Gram + threshold from compaction)")
@@ -89,7 +90,17 @@ def main():
     ej.reserve(n + nq, d)
     expect_pairs = int(n * (S / 2 * (n / spec["n"]) + 1)) if args.mode != "join" else int(nq * S * (n / spec["n"]) * 2)
     capacity = int(expect_pairs * 1.5) + (1 << 20)
-    if args.mode == "join":
+    if args.mode == "split":
+        ej.reserve(2 * n, 3 * ((d + 63) // 64 * 64))
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(datagen.data_seed(w))
+        X32 = Xd.view(torch.float16).to(torch.float32)
+        X32 += (torch.rand(X32.shape, generator=gen, device="cuda:0", dtype=torch.float32) - 0.5) * 2.0 ** -12
+        pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
+        dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
+        npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        step = lambda: ej.selfjoin_pairs_f32(X32, eps, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
+    elif args.mode == "join":
         Qd = torch.from_numpy(np.ascontiguousarray(X[n:]).view(np.int16)).to("cuda:0")
         pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
         dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
@@ -121,7 +132,7 @@ def main():
     ej.set_profiling(False)
     found = int(npairs.cpu()[0])
     e2e = None
-    if args.e2e and args.mode == "pairs":
+    if args.e2e and args.mode == "pairs":  # (not for the other modes)
         # End-to-end response time in the paper's sense (Section 4.1.1: transfers and result storage included).
         Xh = torch.from_numpy(X[:n].view(np.int16)).pin_memory()
         m = min(found, capacity)
@@ -146,7 +157,7 @@ def main():
     dk = (d + 63) // 64 * 64
     tiles = pkg.tiles_evaluated(n) if args.mode != "join" else pkg.tiles_evaluated2(n, nq)
     derived_flop = 2.0 * n * n * d if args.mode != "join" else 2.0 * n * nq * d
-    flop_exec = 2.0 * 256 * 256 * dk * tiles
+    flop_exec = 2.0 * 256 * 256 * dk * tiles * (3 if args.mode == "split" else 1)  # split: hi.hi + lo.hi + hi.lo
     jm = sum(join_ms) / len(join_ms)
     achieved = flop_exec / (jm * 1e-3) / 1e12
     emitted = found + (0 if args.mode == "pairs" else 0)
@@ -161,14 +172,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16",
+        "dtype": "f16" if args.mode != "split" else "f16x2 (split FP32)",
         "accumulate": "f32",
         "data": "synthetic",
         "config": {"workload": f"configs[{w - 1}]: n={n}, d={d}, {spec['kind']}, S={S}, eps={eps:.7g}, mode={args.mode}",
                    "n": n, "d": d, "selectivity_target": S, "eps": eps, "mode": args.mode},
         "pairs_found": found,
         "pairs_per_s": emitted / (ms_per_step * 1e-3),
-        "achieved_selectivity": (2.0 * (found - n) / n) if args.mode == "pairs" else (2.0 * found / n if args.mode == "count" else found / max(nq, 1)),
+        "achieved_selectivity": (2.0 * (found - n) / n) if args.mode in ("pairs", "split") else (2.0 * found / n if args.mode == "count" else found / max(nq, 1)),
         "kernel_ms": {"norms": sum(norm_ms) / len(norm_ms), "join": jm, "join_min": min(join_ms), "join_median": sorted(join_ms)[len(join_ms) // 2]},
         "pairs_write_GBps": (min(found, capacity) * 12 / (jm * 1e-3) / 1e9) if args.mode != "count" else 0.0,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP16_TFLOPS,
@@ -178,7 +189,7 @@ def main():
         out["config"]["queries"] = nq
     if e2e is not None:
         out["end_to_end"] = e2e
-    if not args.no_cpu_baseline and args.mode != "join":
+    if not args.no_cpu_baseline and args.mode not in ("join", "split"):
         rows = args.cpu_rows or max(8, int(2.0e12 / (n * d * 16)))  # ~10-30 s of host work
         out["cpu_baseline"] = cpu_baseline(X[:n], w, eps, rows)
     print(json.dumps(out))

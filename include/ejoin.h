@@ -105,6 +105,20 @@ int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
 int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
                          uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
 
+/* Higher-accuracy variant for FP32 data: the self-join of n FP32 rows (device, row stride ld32 >= d
+ * elements, no padding or alignment required) with every coordinate carried as two FP16 numbers,
+ * x ~ hi + lo, hi = fp16(x), lo = fp16(x - hi) -- 22 significant bits instead of 11, which removes the
+ * FP16 conversion of the inputs as a source of error (the paper names the limited accuracy of FP16
+ * inputs and possible remedies as future work, Section 5).  The inner products are taken as
+ * hi.hi + lo.hi + hi.lo on the matrix cores (FP32 accumulation, 3 x the work of the FP16 join); norms,
+ * threshold, result conventions, capacity / n_pairs / dist2 / counts and the data-range rule
+ * (|x| <= 65504, s < 2^31) are those of ejoin_selfjoin_pairs / ejoin_selfjoin_count.  d <= 16384.
+ * The workspace holds two re-laid-out copies of the split data: 12 * roundup(n,256) * roundup(d,64) bytes. */
+int ejoin_selfjoin_pairs_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps,
+                             uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
+int ejoin_selfjoin_count_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps,
+                             uint32_t* counts, uint64_t* total_pairs, void* stream);
+
 /* Two-set join: "points" P (np x d) against "query points" Q (nq x d), the general form of the
  * distance computation of Section 3.1 (fragments of points and of query points; the paper offers
  * the method as a subroutine for such searches, Section 1).  Same layout rules for P and Q as for X

@@ -48,6 +48,10 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.ejoin_selfjoin_count.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
     lib.ejoin_selfjoin_pairs.restype = C.c_int
     lib.ejoin_selfjoin_pairs.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_selfjoin_count_f32.restype = C.c_int
+    lib.ejoin_selfjoin_count_f32.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
+    lib.ejoin_selfjoin_pairs_f32.restype = C.c_int
+    lib.ejoin_selfjoin_pairs_f32.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
     lib.ejoin_join_pairs.restype = C.c_int
     lib.ejoin_join_pairs.argtypes = [vp, vp, i64, i64, vp, i64, i64, i32, f32, vp, vp, u64, vp, vp]
     lib.ejoin_join_count.restype = C.c_int
@@ -178,6 +182,39 @@ class EJoin:
                                                    dist2.data_ptr() if dist2 is not None else None, capacity,
                                                    n_pairs.data_ptr(), self._stream()), self._h)
         return pairs, dist2, n_pairs
+
+    @staticmethod
+    def _x32(X32: torch.Tensor):
+        if X32.dtype != torch.float32 or X32.dim() != 2 or not X32.is_cuda or X32.stride(1) != 1:
+            raise EJoinError("X32 must be a 2-D float32 device tensor with contiguous rows")
+        return X32.shape[0], X32.shape[1], X32.stride(0)
+
+    def selfjoin_pairs_f32(self, X32: torch.Tensor, eps: float, capacity: int, with_dist2: bool = True,
+                           pairs: torch.Tensor | None = None, dist2: torch.Tensor | None = None, n_pairs: torch.Tensor | None = None):
+        """Split-FP16 self-join of FP32 rows; returns like selfjoin_pairs."""
+        n, d, ld = self._x32(X32)
+        capacity = int(capacity)
+        if pairs is None:
+            pairs = torch.empty((max(capacity, 1), 2), dtype=torch.int32, device=X32.device)
+        if dist2 is None and with_dist2:
+            dist2 = torch.empty(max(capacity, 1), dtype=torch.float32, device=X32.device)
+        if n_pairs is None:
+            n_pairs = torch.empty(1, dtype=torch.int64, device=X32.device)
+        self._check(self._lib.ejoin_selfjoin_pairs_f32(self._h, X32.data_ptr(), n, d, ld, float(eps), pairs.data_ptr(),
+                                                       dist2.data_ptr() if dist2 is not None else None, capacity,
+                                                       n_pairs.data_ptr(), self._stream()), self._h)
+        return pairs, dist2, n_pairs
+
+    def selfjoin_count_f32(self, X32: torch.Tensor, eps: float, counts: torch.Tensor | None = None, total: torch.Tensor | None = None):
+        """Split-FP16 neighbour counts of FP32 rows; returns like selfjoin_count."""
+        n, d, ld = self._x32(X32)
+        if counts is None:
+            counts = torch.empty(n, dtype=torch.int32, device=X32.device)
+        if total is None:
+            total = torch.empty(1, dtype=torch.int64, device=X32.device)
+        self._check(self._lib.ejoin_selfjoin_count_f32(self._h, X32.data_ptr(), n, d, ld, float(eps), counts.data_ptr(),
+                                                       total.data_ptr(), self._stream()), self._h)
+        return counts, total
 
     def join_pairs(self, P: torch.Tensor, Q: torch.Tensor, eps: float, capacity: int, d: int | None = None, with_dist2: bool = True,
                    pairs: torch.Tensor | None = None, dist2: torch.Tensor | None = None, n_pairs: torch.Tensor | None = None):

@@ -265,6 +265,82 @@ __global__ void k_pack(const uint16_t* __restrict__ X, int64_t n, int64_t npad, 
   Xp[t] = v;
 }
 
+// Split-FP16 variant (higher accuracy for FP32 inputs).  Each FP32 coordinate is cut into two FP16
+// numbers, x ~ hi + lo with hi = fp16(x), lo = fp16(x - hi) (22 significant bits together), and the
+// inner product is taken as hi.hi + lo.hi + hi.lo (the lo.lo term is below the 22 bits kept).  That is
+// an ordinary inner product of the 3d-dimensional rows A' = [hi | lo | hi] and B' = [hi | hi | lo], so
+// the join kernel runs unchanged on two packed arrays: row operands come from A', column operands from
+// B'.  This kernel writes both arrays straight from the FP32 rows, in the packed k-block layout of
+// k_pack (nkb blocks per part, 3 nkb blocks per array; rows n .. npad-1 and columns d .. are zero).
+// Thread t handles the 8 coordinates of one 16-byte chunk.
+__global__ void k_split_pack(const float* __restrict__ X32, int64_t n, int64_t npad, int32_t d, int64_t ld32, int nkb,
+                             uint4* __restrict__ XpA, uint4* __restrict__ XpB) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)nkb * npad * 4;
+  if (t >= total) return;
+  const int p = (int)(t & 3);
+  const int64_t rk = t >> 2;
+  const int64_t kb = rk / npad, r = rk - kb * npad;
+  const int k0 = (int)kb * KSLICE + ((p ^ swz((int)(r & 255))) << 3);  // first coordinate of the chunk stored at position p
+  half8 hi, lo;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const float x = (r < n && k0 + k < d) ? X32[r * ld32 + k0 + k] : 0.f;
+    const _Float16 h = (_Float16)x;
+    float rest = x - (float)h;
+    asm volatile("" : "+v"(rest));  // the residual is an FP32 number: no fused subtract-convert
+    hi[k] = h;
+    lo[k] = (_Float16)rest;
+  }
+  const uint4 vh = __builtin_bit_cast(uint4, hi), vl = __builtin_bit_cast(uint4, lo);
+  const int64_t part = (int64_t)nkb * npad * 4;
+  XpA[t] = vh;
+  XpA[t + part] = vl;
+  XpA[t + 2 * part] = vh;
+  XpB[t] = vh;
+  XpB[t + part] = vh;
+  XpB[t + 2 * part] = vl;
+}
+
+// Norms for the split variant: s_i = A'_i . B'_i, accumulated by the same MFMA steps in the same
+// order as the join kernel accumulates a_ii (k-blocks in order, two 16-wide steps per block), read
+// from the packed arrays.  One wavefront per 32 consecutive points, like k_norms.
+__global__ __launch_bounds__(256) void k_norms_packed(const uint4* __restrict__ XpA, const uint4* __restrict__ XpB, int64_t n,
+                                                      int64_t npad, int nkb_total, float* __restrict__ s,
+                                                      uint32_t* __restrict__ max_bits) {
+  const int lane = threadIdx.x & 63;
+  const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t row0 = blk * 32;
+  if (row0 >= n) return;
+  const int64_t row = row0 + (lane & 31);  // < npad: rows past n are zero
+  const int hi = lane >> 5, sw = swz((int)(row & 255));
+  float16v acc;
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  for (int kb = 0; kb < nkb_total; ++kb) {
+    const uint4* ra = XpA + ((int64_t)kb * npad + row) * 4;
+    const uint4* rb = XpB + ((int64_t)kb * npad + row) * 4;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int pos = (2 * t + hi) ^ sw;
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ra[pos]), as_half8(rb[pos]), acc, 0, 0, 0);
+    }
+  }
+  const int c = lane & 31;
+  uint32_t bits = 0;
+  if (((c >> 2) & 1) == hi && row0 + c < n) {
+    const int want = 4 * (c >> 3) + (c & 3);
+    float v = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (r == want) v = acc[r];
+    s[row0 + c] = v;
+    bits = v < 0.f ? 0u : __float_as_uint(v);  // (a sum that rounds below zero counts as zero; NaN stays NaN)
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) bits = max(bits, (uint32_t)__shfl_xor((int)bits, off));
+  if (lane == 0) atomicMax(max_bits, bits);
+}
+
 // Dense block of squared distances with the join's arithmetic: one wavefront per 32 x 32 block.
 __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ H,
                                                   const uint32_t* __restrict__ status, int64_t n, int64_t ld, int k16steps,
@@ -981,6 +1057,77 @@ int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const 
   return EJOIN_OK;
 }
 
+// Split-FP16 self-join of FP32 rows (see k_split_pack): the same join kernel on 3 * nkb k-blocks.
+template <bool COUNT>
+int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* pairs, float* dist2,
+                   uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint64_t* total, hipStream_t st) {
+  const int64_t pad = pad_rows(n);
+  const int32_t d3 = 3 * pad_dims(d);
+  int rc = ensure_workspace(ctx, 2 * pad, d3);  // two packed arrays of 3 * nkb data blocks + 1 augmentation block each
+  if (rc != EJOIN_OK) return rc;
+  const int nkb = pad_dims(d) / KSLICE;
+  uint4* XpA = ctx->Xp;
+  uint4* XpB = ctx->Xp + pad * (int64_t)(3 * nkb + 1) * 4;
+  JoinArgs a;
+  memset(&a, 0, sizeof(a));
+  a.XpA = XpA;
+  a.XpB = XpB;
+  a.npadA = a.npadB = pad;
+  a.nA = a.nB = n;
+  a.self = 1;
+  a.status = ctx->status;
+  a.nslices = 3 * nkb;
+  a.thr = -0.5f * (eps * eps);
+  a.ntilesA = a.ntilesB = (uint32_t)(pad / TILE);
+  a.nsbA = a.nsbB = (a.ntilesA + SB - 1) / SB;
+  a.pairs = pairs;
+  a.dist2 = dist2;
+  a.capacity = capacity;
+  a.n_pairs = reinterpret_cast<unsigned long long*>(n_pairs);
+  a.counts = counts;
+  a.total = reinterpret_cast<unsigned long long*>(total);
+  a.xcd_bar = ctx->status + 8;
+  {
+    const int per = 512 / (a.nslices + 1);
+    a.sync_mode = per < 8 ? 8 : (per > 64 ? 64 : per);
+  }
+  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
+  if ((rc = launch_reset(ctx, COUNT ? a.total : a.n_pairs, st)) != EJOIN_OK) return rc;
+  {
+    const int64_t chunks = (int64_t)nkb * pad * 4;
+    hipLaunchKernelGGL(k_split_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X32, n, pad, d, ld32, nkb, XpA, XpB);
+    EJ_TRY(hipGetLastError());
+    const int64_t waves = (n + 31) / 32;
+    hipLaunchKernelGGL(k_norms_packed, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, XpA, XpB, n, pad, 3 * nkb, ctx->s,
+                       ctx->status + 1);
+    EJ_TRY(hipGetLastError());
+  }
+  if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, XpA + (int64_t)3 * nkb * pad * 4, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, XpB + (int64_t)3 * nkb * pad * 4, st)) != EJOIN_OK) return rc;
+  if (COUNT) {
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counts, n, 0u);
+    EJ_TRY(hipGetLastError());
+  }
+  if (ctx->profiling) {
+    EJ_TRY(hipEventRecord(ctx->ev[1], st));
+    EJ_TRY(hipEventRecord(ctx->ev[2], st));
+  }
+  hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
+  EJ_TRY(hipGetLastError());
+  if (ctx->profiling) {
+    EJ_TRY(hipEventRecord(ctx->ev[3], st));
+    ctx->ev_valid = 1;
+  }
+  return EJOIN_OK;
+}
+
+int check_f32(const ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32) {
+  if (!ctx || !X32) return EJOIN_EINVAL;
+  if (n < 1 || n >= (int64_t)0xFFFFFFFFll - TILE || d < 1 || d > 65536 / 4 || ld32 < d) return EJOIN_EINVAL;
+  if ((int64_t)pad_rows(n) * (pad_dims(d) / KSLICE) * 4 / 256 > 0x7FFFFFFFll) return EJOIN_EUNSUPPORTED;
+  return EJOIN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1085,6 +1232,27 @@ int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
   if (!guard.ok) return EJOIN_EHIP;
   return run_join<false>(ctx, X, n, ld, nullptr, 0, 0, d, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
                          static_cast<hipStream_t>(stream));
+}
+
+int ejoin_selfjoin_count_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* counts,
+                             uint64_t* total_pairs, void* stream) {
+  int rc = check_f32(ctx, X32, n, d, ld32);
+  if (rc != EJOIN_OK) return rc;
+  if (!counts || !total_pairs || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join_split<true>(ctx, X32, n, d, ld32, eps, nullptr, nullptr, 0, nullptr, counts, total_pairs, static_cast<hipStream_t>(stream));
+}
+
+int ejoin_selfjoin_pairs_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* pairs,
+                             float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
+  int rc = check_f32(ctx, X32, n, d, ld32);
+  if (rc != EJOIN_OK) return rc;
+  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join_split<false>(ctx, X32, n, d, ld32, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr,
+                               static_cast<hipStream_t>(stream));
 }
 
 int ejoin_join_pairs(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq, int32_t d,
