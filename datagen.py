@@ -34,6 +34,8 @@ WORKLOADS = {
     3: dict(n=1_000_000, d=960, kind="mixture", clusters=1_000, sigma=0.02, selectivity=(16,), eps_from="sample"),
     4: dict(n=2_000_000, d=384, kind="mixture", clusters=2_000, sigma=0.03, selectivity=(16, 128, 1024), eps_from="sample"),
     5: dict(n=5_000_000, d=128, kind="mixture", clusters=10_000, sigma=0.05, selectivity=(64,), eps_from="sample"),
+    # not one of the task's five configurations: a scale test (1.1e9 tiles, two data slices per tile)
+    6: dict(n=12_000_000, d=64, kind="mixture", clusters=20_000, sigma=0.05, selectivity=(64,), eps_from="sample"),
 }
 
 SAMPLE_POINTS = 2048
