@@ -61,6 +61,7 @@ def main():
                     help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points; "
                          "split: higher-accuracy self-join of FP32 data (the workload's points plus seeded sub-FP16 noise), pair list")
     ap.add_argument("--queries", type=int, default=100_000, help="query points of --mode join (same distribution, rows n .. n+queries-1)")
+    ap.add_argument("--prepared", action="store_true", help="--mode join: prepare the point set once (ejoin_set), time the per-batch calls")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
     ap.add_argument("--eps", type=float, default=None, help="override epsilon (0 = output-free run: isolates Gram + threshold from compaction)")
     ap.add_argument("--e2e", action="store_true", help="also time one end-to-end response: pinned host X -> HBM, step, found pairs -> pinned host")
@@ -105,7 +106,11 @@ def main():
         pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
         dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
         npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
-        step = lambda: ej.join_pairs(Xd, Qd, eps, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
+        if args.prepared:
+            pset = ej.prepare(Xd)
+            step = lambda: pset.join_pairs(Qd, eps, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
+        else:
+            step = lambda: ej.join_pairs(Xd, Qd, eps, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
     elif args.mode == "pairs":
         pairs = torch.empty((capacity, 2), dtype=torch.int32, device="cuda:0")
         dist2 = torch.empty(capacity, dtype=torch.float32, device="cuda:0")
@@ -187,6 +192,7 @@ def main():
     }
     if args.mode == "join":
         out["config"]["queries"] = nq
+        out["config"]["prepared_set"] = bool(args.prepared)
     if e2e is not None:
         out["end_to_end"] = e2e
     if not args.no_cpu_baseline and args.mode not in ("join", "split"):

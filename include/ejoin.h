@@ -136,6 +136,23 @@ int ejoin_join_pairs(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp,
 int ejoin_join_count(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq,
                      int32_t d, float eps, uint32_t* counts_p, uint32_t* counts_q, uint64_t* total, void* stream);
 
+/* Prepared point set, for joining many batches of query points against the same points (the use as a
+ * subroutine of searches the paper names, Section 1): ejoin_set_create computes the norms of X and its
+ * re-laid-out copy once (work enqueued on `stream`; X may be released once that work has completed),
+ * ejoin_set_join_pairs / _count then do per call only the work that depends on the query points.
+ * The set owns its device memory (roundup(n,256) * (roundup(d,64) * 2 + 84) bytes) until
+ * ejoin_set_destroy, which the caller invokes after synchronising, and before destroying the context.
+ * Results, arguments and conventions are those of ejoin_join_pairs / ejoin_join_count with P = the set
+ * (d is the set's).  A join writes a small part of the set (the norm terms, rescaled to the larger of
+ * the two sets' largest norms), so calls that use the same set must not overlap.  *out is a host pointer. */
+typedef struct ejoin_set ejoin_set;
+int ejoin_set_create(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, void* stream, ejoin_set** out);
+int ejoin_set_destroy(ejoin_set* set);
+int ejoin_set_join_pairs(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_t nq, int64_t ldq, float eps,
+                         uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
+int ejoin_set_join_count(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_t nq, int64_t ldq, float eps,
+                         uint32_t* counts_p, uint32_t* counts_q, uint64_t* total, void* stream);
+
 /* Dense block of squared distances, for checking Steps 2-3 of Section 3.1 element by element:
  *   out[r * cols + c] = d2(i0 + r, j0 + c),  0 <= r < rows, 0 <= c < cols   (device, rows*cols f32)
  * computed with exactly the arithmetic of the join (so it is bit-identical to the dist2 the join

@@ -52,6 +52,14 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.ejoin_selfjoin_count_f32.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
     lib.ejoin_selfjoin_pairs_f32.restype = C.c_int
     lib.ejoin_selfjoin_pairs_f32.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_set_create.restype = C.c_int
+    lib.ejoin_set_create.argtypes = [vp, vp, i64, i32, i64, vp, C.POINTER(vp)]
+    lib.ejoin_set_destroy.restype = C.c_int
+    lib.ejoin_set_destroy.argtypes = [vp]
+    lib.ejoin_set_join_pairs.restype = C.c_int
+    lib.ejoin_set_join_pairs.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_set_join_count.restype = C.c_int
+    lib.ejoin_set_join_count.argtypes = [vp, vp, vp, i64, i64, f32, vp, vp, vp, vp]
     lib.ejoin_join_pairs.restype = C.c_int
     lib.ejoin_join_pairs.argtypes = [vp, vp, i64, i64, vp, i64, i64, i32, f32, vp, vp, u64, vp, vp]
     lib.ejoin_join_count.restype = C.c_int
@@ -216,6 +224,10 @@ class EJoin:
                                                        total.data_ptr(), self._stream()), self._h)
         return counts, total
 
+    def prepare(self, X: torch.Tensor, d: int | None = None) -> "EJoinSet":
+        """Prepared point set (ejoin_set_create): pack X and compute its norms once, join query batches against it."""
+        return EJoinSet(self, X, d)
+
     def join_pairs(self, P: torch.Tensor, Q: torch.Tensor, eps: float, capacity: int, d: int | None = None, with_dist2: bool = True,
                    pairs: torch.Tensor | None = None, dist2: torch.Tensor | None = None, n_pairs: torch.Tensor | None = None):
         """Two-set join; returns (pairs int32[capacity, 2]: (index into P, index into Q), dist2 or None, n_pairs int64[1])."""
@@ -268,3 +280,55 @@ class EJoin:
         a, b = C.c_float(), C.c_float()
         self._check(self._lib.ejoin_last_kernel_ms(self._h, C.byref(a), C.byref(b)), self._h)
         return float(a.value), float(b.value)
+
+
+class EJoinSet:
+    """A prepared point set (ejoin_set).  Joins that use the same set must not overlap."""
+
+    def __init__(self, ej: EJoin, X: torch.Tensor, d: int | None = None):
+        self._ej = ej
+        self.n, self.d, ld = ej._x(X, d)
+        h = C.c_void_p()
+        ej._check(ej._lib.ejoin_set_create(ej._h, X.data_ptr(), self.n, self.d, ld, ej._stream(), C.byref(h)), ej._h)
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None) and getattr(self._ej, "_h", None):
+            torch.cuda.synchronize(self._ej.device)
+            self._ej._lib.ejoin_set_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def join_pairs(self, Q: torch.Tensor, eps: float, capacity: int, with_dist2: bool = True, pairs: torch.Tensor | None = None,
+                   dist2: torch.Tensor | None = None, n_pairs: torch.Tensor | None = None):
+        """Like EJoin.join_pairs with P = this set."""
+        ej = self._ej
+        n_q, d_q, ldq = ej._x(Q, self.d)
+        capacity = int(capacity)
+        if pairs is None:
+            pairs = torch.empty((max(capacity, 1), 2), dtype=torch.int32, device=Q.device)
+        if dist2 is None and with_dist2:
+            dist2 = torch.empty(max(capacity, 1), dtype=torch.float32, device=Q.device)
+        if n_pairs is None:
+            n_pairs = torch.empty(1, dtype=torch.int64, device=Q.device)
+        ej._check(ej._lib.ejoin_set_join_pairs(ej._h, self._h, Q.data_ptr(), n_q, ldq, float(eps), pairs.data_ptr(),
+                                               dist2.data_ptr() if dist2 is not None else None, capacity, n_pairs.data_ptr(),
+                                               ej._stream()), ej._h)
+        return pairs, dist2, n_pairs
+
+    def join_count(self, Q: torch.Tensor, eps: float, want_counts_q: bool = True):
+        """Like EJoin.join_count with P = this set: (counts_p, counts_q or None, total)."""
+        ej = self._ej
+        n_q, d_q, ldq = ej._x(Q, self.d)
+        counts_p = torch.empty(self.n, dtype=torch.int32, device=Q.device)
+        counts_q = torch.empty(n_q, dtype=torch.int32, device=Q.device) if want_counts_q else None
+        total = torch.empty(1, dtype=torch.int64, device=Q.device)
+        ej._check(ej._lib.ejoin_set_join_count(ej._h, self._h, Q.data_ptr(), n_q, ldq, float(eps), counts_p.data_ptr(),
+                                               counts_q.data_ptr() if counts_q is not None else None, total.data_ptr(),
+                                               ej._stream()), ej._h)
+        return counts_p, counts_q, total

@@ -106,6 +106,11 @@ __global__ void k_reset(uint32_t* status_and_max, unsigned long long* c0) {
   }
 }
 
+// Folds the largest norm of a prepared set (stored as FP32 bits) into the running maximum of a call.
+__global__ void k_merge_max(uint32_t* max_bits, const uint32_t* set_max) {
+  if (threadIdx.x == 0) atomicMax(max_bits, *set_max);
+}
+
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -863,6 +868,18 @@ struct ejoin_ctx {
   char hip_error[256];
 };
 
+// A point set prepared once for many joins: its packed copy (data k-blocks + room for the augmentation
+// block, which depends on the other set of each join and is rewritten per call), norms and largest norm.
+struct ejoin_set {
+  ejoin_ctx* ctx;
+  int64_t n, pad;
+  int32_t d;
+  uint4* Xp;
+  float* s;
+  uint4* H;
+  uint32_t* max_bits;  // device: FP32 bits of the largest norm
+};
+
 namespace {
 
 int fail_hip(ejoin_ctx* ctx, hipError_t e, const char* what) {
@@ -1121,6 +1138,74 @@ int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64
   return EJOIN_OK;
 }
 
+// Two-set join of a prepared point set with query points given as FP16 rows.
+template <bool COUNT>
+int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, int64_t nQ, int64_t ldQ, float eps, uint32_t* pairs,
+                      float* dist2, uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint32_t* counts_b, uint64_t* total,
+                      hipStream_t st) {
+  const int32_t d = P->d;
+  const int64_t padQ = pad_rows(nQ);
+  int rc = ensure_workspace(ctx, padQ, d);
+  if (rc != EJOIN_OK) return rc;
+  const int nkb = (int)(pad_dims(d) / KSLICE);
+  JoinArgs a;
+  memset(&a, 0, sizeof(a));
+  a.XpA = P->Xp;
+  a.XpB = ctx->Xp;
+  a.npadA = P->pad;
+  a.npadB = padQ;
+  a.nA = P->n;
+  a.nB = nQ;
+  a.self = 0;
+  a.status = ctx->status;
+  a.nslices = nkb;
+  a.thr = -0.5f * (eps * eps);
+  a.ntilesA = (uint32_t)(P->pad / TILE);
+  a.ntilesB = (uint32_t)(padQ / TILE);
+  a.nsbA = (a.ntilesA + SB - 1) / SB;
+  a.nsbB = (a.ntilesB + SB - 1) / SB;
+  a.pairs = pairs;
+  a.dist2 = dist2;
+  a.capacity = capacity;
+  a.n_pairs = reinterpret_cast<unsigned long long*>(n_pairs);
+  a.counts = counts;
+  a.counts_b = counts_b;
+  a.total = reinterpret_cast<unsigned long long*>(total);
+  a.xcd_bar = ctx->status + 8;
+  {
+    const int per = 512 / (a.nslices + 1);
+    a.sync_mode = per < 8 ? 8 : (per > 64 ? 64 : per);
+  }
+  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
+  if ((rc = launch_reset(ctx, COUNT ? a.total : a.n_pairs, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_norms(ctx, XQ, nQ, d, ldQ, ctx->s, ctx->status + 1, st)) != EJOIN_OK) return rc;
+  hipLaunchKernelGGL(k_merge_max, dim3(1), dim3(64), 0, st, ctx->status + 1, P->max_bits);
+  EJ_TRY(hipGetLastError());
+  // the augmentation rows of both sets are scaled to the largest norm of the two: those of the prepared set are rewritten
+  if ((rc = launch_aux(ctx, P->s, P->n, P->H, P->Xp + (int64_t)nkb * P->pad * 4, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_aux(ctx, ctx->s, nQ, ctx->H, ctx->Xp + (int64_t)nkb * padQ * 4, st)) != EJOIN_OK) return rc;
+  if ((rc = launch_pack(ctx, XQ, nQ, ldQ, nkb, ctx->Xp, st)) != EJOIN_OK) return rc;
+  if (COUNT) {
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((P->n + 255) / 256)), dim3(256), 0, st, counts, P->n, 0u);
+    EJ_TRY(hipGetLastError());
+    if (counts_b) {
+      hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nQ + 255) / 256)), dim3(256), 0, st, counts_b, nQ, 0u);
+      EJ_TRY(hipGetLastError());
+    }
+  }
+  if (ctx->profiling) {
+    EJ_TRY(hipEventRecord(ctx->ev[1], st));
+    EJ_TRY(hipEventRecord(ctx->ev[2], st));
+  }
+  hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
+  EJ_TRY(hipGetLastError());
+  if (ctx->profiling) {
+    EJ_TRY(hipEventRecord(ctx->ev[3], st));
+    ctx->ev_valid = 1;
+  }
+  return EJOIN_OK;
+}
+
 int check_f32(const ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32) {
   if (!ctx || !X32) return EJOIN_EINVAL;
   if (n < 1 || n >= (int64_t)0xFFFFFFFFll - TILE || d < 1 || d > 65536 / 4 || ld32 < d) return EJOIN_EINVAL;
@@ -1277,6 +1362,78 @@ int ejoin_join_count(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp,
   if (!guard.ok) return EJOIN_EHIP;
   return run_join<true>(ctx, P, np, ldp, Q, nq, ldq, d, eps, nullptr, nullptr, 0, nullptr, counts_p, counts_q, total,
                         static_cast<hipStream_t>(stream));
+}
+
+int ejoin_set_create(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, void* stream, ejoin_set** out) {
+  if (!out) return EJOIN_EINVAL;
+  *out = nullptr;
+  int rc = check_common(ctx, X, n, d, ld);
+  if (rc != EJOIN_OK) return rc;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ejoin_set* set = new (std::nothrow) ejoin_set();
+  if (!set) return EJOIN_ENOMEM;
+  set->ctx = ctx;
+  set->n = n;
+  set->pad = pad_rows(n);
+  set->d = d;
+  const int nkb = (int)(pad_dims(d) / KSLICE);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&set->Xp), (size_t)set->pad * (size_t)(nkb + 1) * 64);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&set->s), (size_t)set->pad * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&set->H), (size_t)set->pad * sizeof(uint4));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&set->max_bits), 256);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    (void)ejoin_set_destroy(set);
+    return e == hipErrorOutOfMemory ? EJOIN_ENOMEM : fail_hip(ctx, e, "hipMalloc(prepared set)");
+  }
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, set->max_bits, (int64_t)1, 0u);
+  rc = (hipGetLastError() == hipSuccess) ? EJOIN_OK : EJOIN_EHIP;
+  if (rc == EJOIN_OK) rc = launch_norms(ctx, X, n, d, ld, set->s, set->max_bits, st);
+  if (rc == EJOIN_OK) rc = launch_pack(ctx, X, n, ld, nkb, set->Xp, st);
+  if (rc != EJOIN_OK) {
+    (void)hipDeviceSynchronize();
+    (void)ejoin_set_destroy(set);
+    return rc;
+  }
+  *out = set;
+  return EJOIN_OK;
+}
+
+int ejoin_set_destroy(ejoin_set* set) {
+  if (!set) return EJOIN_EINVAL;
+  DeviceGuard guard(set->ctx->device);
+  if (set->Xp) (void)hipFree(set->Xp);
+  if (set->s) (void)hipFree(set->s);
+  if (set->H) (void)hipFree(set->H);
+  if (set->max_bits) (void)hipFree(set->max_bits);
+  delete set;
+  return EJOIN_OK;
+}
+
+int ejoin_set_join_pairs(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_t nq, int64_t ldq, float eps, uint32_t* pairs,
+                         float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
+  if (!ctx || !P || P->ctx != ctx) return EJOIN_EINVAL;
+  int rc = check_common(ctx, Q, nq, P->d, ldq);
+  if (rc != EJOIN_OK) return rc;
+  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join_prepared<false>(ctx, P, Q, nq, ldq, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
+                                  static_cast<hipStream_t>(stream));
+}
+
+int ejoin_set_join_count(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_t nq, int64_t ldq, float eps, uint32_t* counts_p,
+                         uint32_t* counts_q, uint64_t* total, void* stream) {
+  if (!ctx || !P || P->ctx != ctx) return EJOIN_EINVAL;
+  int rc = check_common(ctx, Q, nq, P->d, ldq);
+  if (rc != EJOIN_OK) return rc;
+  if (!counts_p || !total || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join_prepared<true>(ctx, P, Q, nq, ldq, eps, nullptr, nullptr, 0, nullptr, counts_p, counts_q, total,
+                                 static_cast<hipStream_t>(stream));
 }
 
 int ejoin_convert_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, const float* center, float scale,

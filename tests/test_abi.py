@@ -45,3 +45,18 @@ def test_binding_refuses_to_run_without_a_gpu():
         pytest.skip("a GPU is visible")
     with pytest.raises(pkg.EJoinError):
         pkg.EJoin(0)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/ejoin.h compiles as C89-with-stdint and as C++ and declares the same prototypes the library was built from."""
+    import shutil
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "ejoin.h"\n'
+                   "int use(void) { ejoin_ctx* c = 0; int st = 0; return ejoin_status(c, &st) + (int)ejoin_tiles_evaluated(1) + EJOIN_OK; }\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, "-c", str(src), "-o", str(tmp_path / "a.o")], check=True)
+    if shutil.which("g++"):
+        cpp = tmp_path / "use_header.cpp"
+        cpp.write_text(src.read_text())
+        subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-I", inc, "-c", str(cpp), "-o", str(tmp_path / "b.o")], check=True)

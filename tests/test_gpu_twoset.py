@@ -130,3 +130,51 @@ def test_two_set_rejects_mismatched_inputs(ej):
     B = torch.zeros((10, 192), dtype=torch.float16, device="cuda")
     with pytest.raises(pkg.EJoinError):
         ej.join_pairs(A, B, 1.0, 10)
+
+
+def test_prepared_set_gives_the_results_of_the_plain_two_set_join(ej):
+    """Three query batches against one prepared set, the second with norms far above the set's (the norm
+    terms of the set are rescaled per call), then the first again: each bit-identical to ejoin_join_pairs."""
+    rng = np.random.default_rng(77)
+    d = 100
+    XP = np.zeros((3000, 128), dtype=np.uint16)
+    XP[:, :d] = rng.random((3000, d), dtype=np.float32).astype(np.float16).view(np.uint16)
+    batches = []
+    for n_q, scale in [(700, 1.0), (1300, 30.0), (257, 0.05)]:
+        XQ = np.zeros((n_q, 128), dtype=np.uint16)
+        XQ[:, :d] = (rng.random((n_q, d), dtype=np.float32) * np.float32(scale)).astype(np.float16).view(np.uint16)
+        batches.append(XQ)
+    Pd = dev(XP)
+    pset = ej.prepare(Pd, d=d)
+    P = orc.decode(XP[:, :d])
+    for k in (0, 1, 2, 0):
+        XQ = batches[k]
+        Q = orc.decode(XQ[:, :d])
+        eps = orc.eps_for_pair_rank(orc.dist2_block2(P, Q, 0, 3000, 0, XQ.shape[0]).ravel(), 2000)
+        a = ej.join_pairs(Pd, dev(XQ), float(eps), 50000, d=d)
+        torch.cuda.synchronize()
+        ap, ad2, af = parity.to_host_pairs(*a)
+        b = pset.join_pairs(dev(XQ), float(eps), 50000)
+        torch.cuda.synchronize()
+        assert ej.status() == 0
+        bp, bd2, bf = parity.to_host_pairs(*b)
+        assert af == bf
+        oa, ob = np.argsort(orc.pair_keys(ap)), np.argsort(orc.pair_keys(bp))
+        assert np.array_equal(ap[oa], bp[ob]) and np.array_equal(ad2[oa], bd2[ob])
+        # and against the oracle
+        op, od2 = orc.join_pairs(P, Q, eps)
+        check_two_set(P, Q, eps, bp, bd2, op, od2)
+        cp, cq, total = pset.join_count(dev(XQ), float(eps))
+        torch.cuda.synchronize()
+        assert int(total.cpu()[0]) == bf
+        assert np.array_equal(cp.cpu().numpy().view(np.uint32), np.bincount(bp[:, 0], minlength=3000))
+        assert np.array_equal(cq.cpu().numpy().view(np.uint32), np.bincount(bp[:, 1], minlength=XQ.shape[0]))
+    pset.close()
+    # a set belongs to its context, and d comes from the set
+    import paper_2508_21230_amd as pkg
+    other = pkg.EJoin(0)
+    s2 = other.prepare(Pd, d=d)
+    with pytest.raises(pkg.EJoinError):
+        ej._check(ej._lib.ejoin_set_join_pairs(ej._h, s2._h, Pd.data_ptr(), 10, 128, 1.0, Pd.data_ptr(), None, 1, Pd.data_ptr(), None), ej._h)
+    s2.close()
+    other.close()
