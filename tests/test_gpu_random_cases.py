@@ -85,3 +85,40 @@ def test_random_two_set_join(ej, seed):
     gp, gd2, found = parity.to_host_pairs(pairs, d2, npairs)
     assert found == gp.shape[0]
     check_two_set(P, Q, eps, gp, gd2, op, od2)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_multi_tile_dense_output_and_overflow(ej, seed):
+    """5000 .. 9500 points (every workgroup walks several tiles), up to hundreds of neighbours per point, and in a
+    third of the cases a result buffer half the size needed: the count keeps running, what was written is valid."""
+    rng = np.random.default_rng(70_000 + seed)
+    d = int(rng.choice([16, 64, 65, 128, 192]))
+    n = int(rng.integers(5000, 9500))
+    ld = (d + 63) // 64 * 64
+    X = draw_points(rng, n, d, ld)
+    P = orc.decode(X[:, :d])
+    S = float(rng.choice([2, 40, 300]))
+    eps = orc.select_eps_sample(P[np.sort(rng.choice(n, size=1500, replace=False))], S, n)
+    ora_pairs, ora_d2 = orc.selfjoin_pairs(P, eps)
+    small_cap = bool(rng.integers(0, 3) == 0)
+    cap = (ora_pairs.shape[0] // 2) if small_cap else ora_pairs.shape[0] * 2 + 1024
+    print(f"random multi-tile seed={seed} n={n} d={d} S={S} eps={eps} pairs={ora_pairs.shape[0]} cap={cap}", flush=True)
+    pairs, d2, npairs = ej.selfjoin_pairs(dev(X), float(eps), cap, d=d)
+    torch.cuda.synchronize()
+    assert ej.status() == 0
+    gp, gd2, found = parity.to_host_pairs(pairs, d2, npairs)
+    if small_cap:
+        assert found > cap and gp.shape[0] == cap
+        kg = orc.pair_keys(gp)
+        assert np.unique(kg).size == kg.size
+        extra = gp[~np.isin(kg, orc.pair_keys(ora_pairs))]
+        if extra.size:
+            s = orc.norms(P)
+            d2x = np.array([orc.dist2(P, int(i), int(j)) for i, j in extra])
+            assert parity.in_band(d2x, eps, s[extra[:, 0]] + s[extra[:, 1]], s.max()).all()
+    else:
+        assert found == gp.shape[0]
+        parity.check_pair_sets(P, eps, gp, gd2, ora_pairs, ora_d2)
+    counts, total = ej.selfjoin_count(dev(X), float(eps), d=d)
+    torch.cuda.synchronize()
+    assert int(total.cpu()[0]) == found - n
