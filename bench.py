@@ -61,6 +61,7 @@ def main():
                     help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points; "
                          "split: higher-accuracy self-join of FP32 data (the workload's points plus seeded sub-FP16 noise), pair list")
     ap.add_argument("--queries", type=int, default=100_000, help="query points of --mode join (same distribution, rows n .. n+queries-1)")
+    ap.add_argument("--graph", action="store_true", help="capture one step in a HIP graph and time replays (launch-bound small workloads)")
     ap.add_argument("--prepared", action="store_true", help="--mode join: prepare the point set once (ejoin_set), time the per-batch calls")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
     ap.add_argument("--eps", type=float, default=None, help="override epsilon (0 = output-free run: isolates Gram + threshold from compaction)")
@@ -124,17 +125,42 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ej.set_profiling(True)
     join_ms, norm_ms = [], []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+    if args.graph:
+        # the library enqueues kernels only (workspace reserved above), so a step can be captured and replayed
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ej.set_profiling(True)  # kernel times from one eager step (events are not recorded inside a graph)
         step()
-        a, b = ej.last_kernel_ms()  # waits for this step's events (HIP events on the launch stream)
+        a, b = ej.last_kernel_ms()
         norm_ms.append(a)
         join_ms.append(b)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ej.set_profiling(False)
+        ej.set_profiling(False)
+    else:
+        ej.set_profiling(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+            a, b = ej.last_kernel_ms()  # waits for this step's events (HIP events on the launch stream)
+            norm_ms.append(a)
+            join_ms.append(b)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ej.set_profiling(False)
     found = int(npairs.cpu()[0])
     e2e = None
     if args.e2e and args.mode == "pairs":  # (not for the other modes)
@@ -180,6 +206,7 @@ def main():
         "dtype": "f16" if args.mode != "split" else "f16x2 (split FP32)",
         "accumulate": "f32",
         "data": "synthetic",
+        "hip_graph": bool(args.graph),
         "config": {"workload": f"configs[{w - 1}]: n={n}, d={d}, {spec['kind']}, S={S}, eps={eps:.7g}, mode={args.mode}",
                    "n": n, "d": d, "selectivity_target": S, "eps": eps, "mode": args.mode},
         "pairs_found": found,

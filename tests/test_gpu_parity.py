@@ -377,3 +377,48 @@ def test_centring_and_scaling_recover_accuracy_on_offset_data(ej):
         acc[name] = orc.overlap_accuracy(n, want, pairs)
     assert acc["raw"] < 0.9
     assert acc["centred"] > 0.99 and acc["centred_scaled"] >= acc["centred"] - 1e-3
+
+
+def test_join_calls_can_be_captured_in_a_hip_graph_and_replayed(ej):
+    """With the workspace reserved a join enqueues kernels only (no allocation, no memset node), so a caller
+    may capture it; every replay, on new data in the same buffers, must equal the eager result."""
+    rng = np.random.default_rng(61)
+    n, d = 3000, 128
+    ej.reserve(n, d)
+    Xd = torch.empty((n, d), dtype=torch.int16, device="cuda")
+    cap = 200000
+    pairs = torch.empty((cap, 2), dtype=torch.int32, device="cuda")
+    d2 = torch.empty(cap, dtype=torch.float32, device="cuda")
+    npairs = torch.zeros(1, dtype=torch.int64, device="cuda")
+    counts = torch.empty(n, dtype=torch.int32, device="cuda")
+    total = torch.zeros(1, dtype=torch.int64, device="cuda")
+    eps = 3.9
+    datasets = [rng.random((n, d), dtype=np.float32).astype(np.float16).view(np.int16) for _ in range(3)]
+    Xd.copy_(torch.from_numpy(datasets[0]))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream, as torch asks
+        ej.selfjoin_pairs(Xd, eps, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
+        ej.selfjoin_count(Xd, eps, counts=counts, total=total)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ej.selfjoin_pairs(Xd, eps, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
+        ej.selfjoin_count(Xd, eps, counts=counts, total=total)
+    for rep in range(4):
+        X = datasets[rep % 3]
+        Xd.copy_(torch.from_numpy(X))
+        g.replay()
+        torch.cuda.synchronize()
+        gp, gd2, found = parity.to_host_pairs(pairs, d2, npairs)
+        gc, gt = counts.cpu().numpy().copy(), int(total.cpu()[0])
+        # eager run on the same data (own buffers), with host synchronisation in between
+        ep, ed2, en = ej.selfjoin_pairs(Xd, eps, cap)
+        ec, et = ej.selfjoin_count(Xd, eps)
+        torch.cuda.synchronize()
+        hp, hd2, hfound = parity.to_host_pairs(ep, ed2, en)
+        assert found == hfound and found > n and gt == int(et.cpu()[0]) == found - n
+        oa, ob = np.argsort(orc.pair_keys(gp)), np.argsort(orc.pair_keys(hp))
+        assert np.array_equal(gp[oa], hp[ob]) and np.array_equal(gd2[oa], hd2[ob])
+        assert np.array_equal(gc, ec.cpu().numpy())
