@@ -13,7 +13,9 @@ statistic of Section 4.5.
 Pins (tests/test_oracle_*.py): exhaustive fp16 decode against two independent decoders;
 exact rational arithmetic (fractions.Fraction) on small inputs; closed forms (identical
 points, axis-aligned points, a 1-D lattice with a closed-form pair count, eps = 0, eps >= sqrt(d));
-symmetry; counts == histogram of the pair list; U[0,1) moments of D2.
+symmetry; counts == histogram of the pair list; U[0,1) moments of D2; the two-set join against the
+self-join of the stacked sets and against exact rational arithmetic; the FP32 -> FP16 ingestion
+(convert_f32) against an independent round-to-nearest-even encoder.  No function here is unpinned.
 """
 from __future__ import annotations
 
