@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "ejoin.h"
+#include "tile_cursor.h"
 
 namespace {
 
@@ -40,7 +41,7 @@ constexpr int KSLICE = 32;    // coordinates per LDS stage (64 B per row)
 constexpr int NSTAGE = EJOIN_ABL_NSTAGE;  // ring of LDS stages; NSTAGE-1 slices are in flight from L2/HBM
 constexpr int DIST = NSTAGE - 1;
 constexpr int THREADS = 512;  // 8 wavefronts: 2 (rows) x 4 (columns), wave tile 128 x 64
-constexpr int SB = 16;        // tiles per super-block edge (one super-block = 256 tiles = one pass of the chip)
+constexpr int SB = (int)EJ_SB;
 constexpr int PANEL_BYTES = TILE * KSLICE * 2;  // 16 KB : one operand panel of one stage
 constexpr int STAGE_BYTES = 2 * PANEL_BYTES;    // A panel + B panel
 constexpr int DUMP_OFF = NSTAGE * STAGE_BYTES;  // 1 KB that absorbs the copies issued past the end of the work
@@ -48,7 +49,7 @@ constexpr int STG_OFF = DUMP_OFF + 1024;        // per-wave result staging: STG_
 constexpr int STG_CAP = 128;
 constexpr int STG_WAVE_BYTES = STG_CAP * 12;
 constexpr int LDS_BYTES = STG_OFF + 8 * STG_WAVE_BYTES;
-constexpr int NUM_XCD = 8;
+constexpr int NUM_XCD = (int)EJ_NUM_XCD;
 static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 static_assert(NSTAGE == 3 || NSTAGE == 4, "the slice pipeline reads one slice ahead: at least two slices in flight");
 
@@ -77,7 +78,6 @@ struct JoinArgs {
   int nslices;  // roundup(d, 64) / 32 : k-blocks of data (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntilesA, ntilesB;  // ceil(n / TILE)
-  uint32_t nsbA, nsbB;        // ceil(ntiles / SB)
   // pair mode
   uint32_t* pairs;
   float* dist2;
@@ -381,100 +381,6 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
 // ------------------------------------------------------------------------------------------
 // The join kernel
 // ------------------------------------------------------------------------------------------
-// Work distribution (the counterpart of the paper's work queue that orders block tiles in small
-// squares for L2 reuse, Section 3.3.1, re-derived for 8 XCDs with private 4 MB L2s):
-//   * the upper triangle of the tile grid is cut into super-blocks of 16 x 16 tiles, enumerated
-//     row-major; one super-block is one pass of the 256 CUs, so at any time the chip works on
-//     (16+16) x 256 rows of X, which the memory-side cache holds;
-//   * inside a super-block each XCD owns an 8 x 4 rectangle of tiles (12 row panels shared by its
-//     32 CUs through its own L2); the rectangle's position rotates with the super-block index so
-//     that partially empty (diagonal, ragged) super-blocks do not starve the same XCD every time;
-//   * workgroup w runs on XCD w % 8 (hardware round-robin, verified on device).  The non-empty tiles
-//     of an XCD's rectangles, in super-block order, form a list; workgroup number k of the XCD takes
-//     entries k, k + 32, k + 64, ... of it.  So every workgroup of an XCD computes the same number of
-//     tiles (+-1), and at any time the 32 of them sit on 32 consecutive entries -- one rectangle,
-//     or the end of one and the start of the next.  That keeps them in step without any
-//     synchronisation or queue, which is what makes the panels they share hit in L2: a schedule
-//     that lets workgroups skip empty tiles individually drifts apart by many tiles and the L2
-//     hit rate collapses (measured: 16 % instead of ~75 %).
-struct TileCursor {
-  uint32_t xcd, wpx;     // this workgroup's XCD; workgroups per XCD
-  uint32_t self, nsbA, nsbB, ntA, ntB;
-  uint64_t target;       // position of this workgroup's next tile in the XCD's list
-  uint64_t rank0;        // position of the first non-empty tile of the current super-block's rectangle
-  uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
-  uint32_t start, wpx_all;  // (row-major ablation only) first tile and stride of this workgroup
-  __device__ void init(uint32_t block, uint32_t nblocks, const JoinArgs& a) {
-    start = block;
-    wpx_all = nblocks;
-    xcd = block % NUM_XCD;
-    wpx = (nblocks - xcd + NUM_XCD - 1) / NUM_XCD;  // workgroups with this XCD id
-    self = a.self;
-    nsbA = a.nsbA;
-    nsbB = a.nsbB;
-    ntA = a.ntilesA;
-    ntB = a.ntilesB;
-    target = block / NUM_XCD;
-    rank0 = 0;
-    P = Q = sbi = 0;
-  }
-  // self-join: upper triangle (I <= J); two sets: the whole ntA x ntB grid
-  __device__ bool cell_ok(uint32_t I, uint32_t J) const { return self ? (I <= J && J < ntB) : (I < ntA && J < ntB); }
-  // next tile of this workgroup; false when the work is exhausted
-  __device__ bool next(uint32_t& I, uint32_t& J) {
-#ifdef EJOIN_ABL_ROWMAJOR_TILES
-    // tiles of the triangle (or grid) in row-major order, tile t to workgroup t % nblocks; P, Q hold the
-    // row and column of this workgroup's next tile, rank0 the stride
-    if (rank0 == 0) {  // first call
-      rank0 = (uint64_t)wpx_all;
-      P = 0;
-      Q = start;
-    } else {
-      Q += (uint32_t)rank0;
-    }
-    while (P < ntA && Q >= ntB) {
-      Q -= ntB;
-      ++P;
-      if (self) Q += P;  // row P of the triangle starts at column P
-    }
-    if (P >= ntA) return false;
-    I = __builtin_amdgcn_readfirstlane(P);
-    J = __builtin_amdgcn_readfirstlane(Q);
-    return true;
-#endif
-    while (P < nsbA) {
-      const uint32_t xp = (xcd + sbi) & 7;
-      const uint32_t I0 = P * SB + (xp >> 2) * 8, J0 = Q * SB + (xp & 3) * 4;
-      // may the rectangle hold empty cells?
-      const bool special = self ? ((P == Q) || (J0 + 4 > ntB)) : ((I0 + 8 > ntA) || (J0 + 4 > ntB));
-      uint32_t v = 32;
-      if (special) {
-        v = 0;
-        for (uint32_t c = 0; c < 32; ++c) v += cell_ok(I0 + (c >> 2), J0 + (c & 3)) ? 1u : 0u;
-      }
-      if (target < rank0 + v) {
-        uint32_t q = (uint32_t)(target - rank0), c = q;
-        if (special) {
-          for (c = 0; c < 32; ++c)
-            if (cell_ok(I0 + (c >> 2), J0 + (c & 3)) && q-- == 0) break;
-        }
-        // every lane computes the same values; say so to the compiler (they feed scalar operands)
-        I = __builtin_amdgcn_readfirstlane(I0 + (c >> 2));
-        J = __builtin_amdgcn_readfirstlane(J0 + (c & 3));
-        target += wpx;
-        return true;
-      }
-      rank0 += v;
-      ++sbi;
-      if (++Q == nsbB) {  // super-blocks row-major; the self-join starts each row on the diagonal
-        ++P;
-        Q = self ? P : 0;
-      }
-    }
-    return false;
-  }
-};
-
 // Workgroup barrier without the fences of __syncthreads(): those make the compiler wait for every
 // outstanding global->LDS copy (vmcnt(0)) at each barrier, which would serialise the copy pipeline.
 // The kernel orders its LDS traffic itself: copies are certified with counted vmcnt waits before the
@@ -627,7 +533,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 
   // ---------------- prologue
   TileCursor tc;
-  tc.init(blockIdx.x, gridDim.x, a);
+  tc.init(blockIdx.x, gridDim.x, (uint32_t)a.self, a.ntilesA, a.ntilesB);
   uint32_t I = 0, J = 0, In = 0, Jn = 0;
   bool have = tc.next(I, J);
   // a workgroup that leaves (now, or after its last tile) releases every later alignment of its XCD
@@ -1024,8 +930,6 @@ int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const 
   a.thr = -0.5f * (eps * eps);
   a.ntilesA = (uint32_t)(padA / TILE);
   a.ntilesB = (uint32_t)(a.npadB / TILE);
-  a.nsbA = (a.ntilesA + SB - 1) / SB;
-  a.nsbB = (a.ntilesB + SB - 1) / SB;
   a.pairs = pairs;
   a.dist2 = dist2;
   a.capacity = capacity;
@@ -1096,7 +1000,6 @@ int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64
   a.nslices = 3 * nkb;
   a.thr = -0.5f * (eps * eps);
   a.ntilesA = a.ntilesB = (uint32_t)(pad / TILE);
-  a.nsbA = a.nsbB = (a.ntilesA + SB - 1) / SB;
   a.pairs = pairs;
   a.dist2 = dist2;
   a.capacity = capacity;
@@ -1162,8 +1065,6 @@ int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, in
   a.thr = -0.5f * (eps * eps);
   a.ntilesA = (uint32_t)(P->pad / TILE);
   a.ntilesB = (uint32_t)(padQ / TILE);
-  a.nsbA = (a.ntilesA + SB - 1) / SB;
-  a.nsbB = (a.ntilesB + SB - 1) / SB;
   a.pairs = pairs;
   a.dist2 = dist2;
   a.capacity = capacity;
