@@ -422,3 +422,22 @@ def test_join_calls_can_be_captured_in_a_hip_graph_and_replayed(ej):
         oa, ob = np.argsort(orc.pair_keys(gp)), np.argsort(orc.pair_keys(hp))
         assert np.array_equal(gp[oa], hp[ob]) and np.array_equal(gd2[oa], hd2[ob])
         assert np.array_equal(gc, ec.cpu().numpy())
+
+
+def test_contexts_and_prepared_sets_release_their_device_memory():
+    import paper_2508_21230_amd as pkg
+    X = torch.zeros((5000, 128), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    for _ in range(20):
+        e = pkg.EJoin(0)
+        e.reserve(200_000, 256)            # ~100 MB of workspace
+        s = e.prepare(X)
+        counts, total = e.selfjoin_count(X, 0.5)
+        torch.cuda.synchronize()
+        s.close()
+        e.close()
+    del counts, total
+    torch.cuda.synchronize()
+    free1 = torch.cuda.mem_get_info()[0]
+    assert free0 - free1 < 64 << 20, f"device memory not returned: {free0 - free1} bytes"
