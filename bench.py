@@ -61,6 +61,9 @@ def main():
                     help="pairs/count: self-join; join: two-set join of the workload's points against --queries query points; "
                          "split: higher-accuracy self-join of FP32 data (the workload's points plus seeded sub-FP16 noise), pair list")
     ap.add_argument("--queries", type=int, default=100_000, help="query points of --mode join (same distribution, rows n .. n+queries-1)")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="also time the same shape on nearly-all-zero points (unique rows, two non-zero coordinates, epsilon 0): "
+                         "operands that barely toggle the matrix cores, to separate the power limit from the kernel's structure")
     ap.add_argument("--graph", action="store_true", help="capture one step in a HIP graph and time replays (launch-bound small workloads)")
     ap.add_argument("--prepared", action="store_true", help="--mode join: prepare the point set once (ejoin_set), time the per-batch calls")
     ap.add_argument("--n", type=int, default=None, help="override the number of points (debugging)")
@@ -222,6 +225,24 @@ def main():
         out["config"]["prepared_set"] = bool(args.prepared)
     if e2e is not None:
         out["end_to_end"] = e2e
+    if args.power_probe and args.mode == "pairs":
+        Z = torch.zeros((n, d), dtype=torch.float16, device="cuda:0")
+        idx = torch.arange(n, device="cuda:0")
+        Z[:, 0] = ((idx % 1024).float() / 1024).half()
+        Z[:, 1] = ((idx // 1024).float() / 8192).half()
+        Zi = Z.view(torch.int16)
+        zstep = lambda: ej.selfjoin_pairs(Zi, 0.0, capacity, pairs=pairs, dist2=dist2, n_pairs=npairs)
+        zstep()
+        torch.cuda.synchronize()
+        ej.set_profiling(True)
+        zms = []
+        for _ in range(max(2, args.steps)):
+            zstep()
+            zms.append(ej.last_kernel_ms()[1])
+        ej.set_profiling(False)
+        zt = sum(zms) / len(zms)
+        out["power_probe"] = {"data": "near-zero points of the same shape, eps = 0", "join_ms": zt,
+                              "achieved": flop_exec / (zt * 1e-3) / 1e12, "frac": flop_exec / (zt * 1e-3) / 1e12 / PEAK_FP16_TFLOPS}
     if not args.no_cpu_baseline and args.mode not in ("join", "split"):
         rows = args.cpu_rows or max(8, int(2.0e12 / (n * d * 16)))  # ~10-30 s of host work
         out["cpu_baseline"] = cpu_baseline(X[:n], w, eps, rows)
