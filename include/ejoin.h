@@ -54,7 +54,7 @@ typedef struct ejoin_ctx ejoin_ctx;
 
 /* Create a context on HIP device `device`.  The context owns a few hundred bytes of device
  * status words and a workspace: 20 bytes per point (the norms s_i and their FP16 split) plus, for
- * the join calls, a re-laid-out copy of X (roundup(n,256) * roundup(d,64) * 2 bytes).  The workspace
+ * the join calls, a re-laid-out copy of X (roundup(n,256) * (roundup(d,64) + 32) * 2 bytes).  The workspace
  * is grown on demand with hipMalloc, or ahead of time by ejoin_reserve.  Host pointer out. */
 int ejoin_create(ejoin_ctx** out, int device);
 
@@ -113,7 +113,8 @@ int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
  * hi.hi + lo.hi + hi.lo on the matrix cores (FP32 accumulation, 3 x the work of the FP16 join); norms,
  * threshold, result conventions, capacity / n_pairs / dist2 / counts and the data-range rule
  * (|x| <= 65504, s < 2^31) are those of ejoin_selfjoin_pairs / ejoin_selfjoin_count.  d <= 16384.
- * The workspace holds two re-laid-out copies of the split data: 12 * roundup(n,256) * roundup(d,64) bytes. */
+ * The workspace holds two re-laid-out copies of the split data, 12 * roundup(n,256) * roundup(d,64) bytes;
+ * ejoin_reserve(ctx, 2 * n, 3 * roundup(d,64)) sizes it ahead of time. */
 int ejoin_selfjoin_pairs_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps,
                              uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
 int ejoin_selfjoin_count_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps,
