@@ -593,21 +593,23 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 
   // One data slice (G-th of the stream).  FIRST: first slice of a tile (accumulators start from zero);
   // LAST: last data slice of a tile (the fragments read ahead are those of the augmentation slice).
-  auto data_slice = [&](auto first_c, auto last_c) {
-    constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+  auto data_slice = [&](auto first_c, auto last_c, auto early_c) {
+    constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value, EARLY = decltype(early_c)::value;
     const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
     // (a) this wave's copies of slice G+1 have landed once only slice G+2's four are outstanding
     if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 2)) : "memory");
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
+    // (c) refill the stage slice G-1 occupied with slice G+DIST.  The two waves that share a SIMD do this at
+    //     different points of the slice, so that one of them always has MFMAs to issue
+    if constexpr (EARLY) issue_one(G + DIST);
     // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
     //     (the second one reads from slice G+1, which barrier (b) has certified)
     load_frags(st_cur, offA[1], offB[1], fa1, fb1);
     if constexpr (FIRST) mma_first(fa0, fb0); else mma_only(fa0, fb0);
     interleave_hint();
-    // (c) refill the stage slice G-1 occupied with slice G+DIST
-    issue_one(G + DIST);
+    if constexpr (!EARLY) issue_one(G + DIST);
     load_frags(st_nxt, LAST ? offA_aug : offA[0], LAST ? offB_aug : offB[0], fa0, fb0);
     mma_only(fa1, fb1);
     interleave_hint();
@@ -618,9 +620,15 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 
   while (have) {
     // ---------------- the nsl >= 2 data slices of the tile
-    data_slice(T_{}, F_{});
-    for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{});
-    data_slice(F_{}, T_{});
+    if (wm) {
+      data_slice(T_{}, F_{}, T_{});
+      for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, T_{});
+      data_slice(F_{}, T_{}, T_{});
+    } else {
+      data_slice(T_{}, F_{}, F_{});
+      for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, F_{});
+      data_slice(F_{}, T_{}, F_{});
+    }
     // ---------------- the augmentation slice: one step, then the filter
     {
       if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
