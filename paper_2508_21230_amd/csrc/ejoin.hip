@@ -433,19 +433,29 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
   // --- global->LDS copies.  One global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 B) = 16 rows of a
-  // panel; in the packed layout that is 1 KB of contiguous global memory.  Wave w copies blocks w and
-  // w + 8 of both 16 KB panels of a slice: 4 copy instructions per wave and slice, always (past the
-  // end of the work they are pointed at a dump area), so the number of outstanding copies is a constant.
+  // panel; in the packed layout that is 1 KB of contiguous global memory.  Only waves 4..7 copy: wave
+  // 4 + c moves blocks c, c + 4, c + 8, c + 12 of both 16 KB panels of a slice, 8 copy instructions per
+  // slice, always (past the end of the work they are pointed at a dump area), so the number of their
+  // outstanding copies is a constant.  The copy unit of the CU accepts the instructions one after the
+  // other and a wave waits at the issue of its own until they are taken; waves 0..3, which share the
+  // SIMDs with 4..7 one to one, issue none and keep the MFMA pipes busy meanwhile.
   const char* XbA = reinterpret_cast<const char*>(a.XpA);
   const char* XbB = reinterpret_cast<const char*>(a.XpB);
   const int64_t kstrideA = a.npadA * 64, kstrideB = a.npadB * 64;  // bytes from one k-block to the next
-  const uint32_t voff0 = lane * 16 + wave * 1024, voff1 = voff0 + 8192;
-  auto issue_slice = [&](const char* pa, const char* pb, uint32_t lds_stage /* LDS address of the stage + wave*1024 */) {
+  const int cw = wave & 3;
+  const bool copier = wave >= 4;
+  const uint32_t voff0 = lane * 16 + cw * 1024;
+  auto issue_slice = [&](const char* pa, const char* pb, uint32_t lds_stage /* LDS address of the stage + cw*1024 */) {
     copy16_to_lds<0>(lds_stage, pa, voff0);
-    copy16_to_lds<8192>(lds_stage, pa, voff1);
+    copy16_to_lds<4096>(lds_stage, pa, voff0 + 4096);
+    copy16_to_lds<8192>(lds_stage, pa, voff0 + 8192);
+    copy16_to_lds<12288>(lds_stage, pa, voff0 + 12288);
     copy16_to_lds<PANEL_BYTES>(lds_stage, pb, voff0);
-    copy16_to_lds<PANEL_BYTES + 8192>(lds_stage, pb, voff1);
+    copy16_to_lds<PANEL_BYTES + 4096>(lds_stage, pb, voff0 + 4096);
+    copy16_to_lds<PANEL_BYTES + 8192>(lds_stage, pb, voff0 + 8192);
+    copy16_to_lds<PANEL_BYTES + 12288>(lds_stage, pb, voff0 + 12288);
   };
+  constexpr int NCOPY = 8;  // copy instructions per slice and copying wave
 
   // --- fragment read addressing (byte offsets inside a stage).  A operand of
   // v_mfma_f32_32x32x16_f16: lane l supplies row l%32, coordinates 8*(l/32) .. +7 of the 16-wide step.
@@ -557,13 +567,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   bool issue_pending = false;   // ... and has finished that one too (see issue_one)
   const char* pa = XbA + (int64_t)I * (TILE * 64);
   const char* pb = XbB + (int64_t)J * (TILE * 64);
-  const uint32_t lds_w = lds0 + wave * 1024;
+  const uint32_t lds_w = lds0 + cw * 1024;
   auto issue_one = [&](uint32_t Gissue) {
+    if (!copier) return;
     if (issue_live) {
       issue_slice(pa, pb, lds_w + (Gissue % NSTAGE) * STAGE_BYTES);
     } else {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, XbA, lane * 16);
+      for (int q = 0; q < NCOPY; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, XbA, lane * 16);
     }
     pa += kstrideA;
     pb += kstrideB;
@@ -585,31 +596,34 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     }
   };
   for (int q = 0; q < DIST; ++q) issue_one(q);
-  // slice 0 has landed when only the copies of the DIST-1 younger slices (4 per slice and wave) are outstanding
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 1)) : "memory");
+  // slice 0 has landed when only the copies of the DIST-1 younger slices (NCOPY per slice and copying wave) are
+  // outstanding (the waves that do not copy have nothing outstanding: their waits pass at once)
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 1)) : "memory");
   __syncthreads();
   half8 fa0[4], fb0[2], fa1[4], fb1[2];
   load_frags(0, offA[0], offB[0], fa0, fb0);
 
   // One data slice (G-th of the stream).  FIRST: first slice of a tile (accumulators start from zero);
   // LAST: last data slice of a tile (the fragments read ahead are those of the augmentation slice).
-  auto data_slice = [&](auto first_c, auto last_c, auto early_c) {
-    constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value, EARLY = decltype(early_c)::value;
+  // COPIER: the instance the copying waves run; the other waves run one without any copy code in it (the
+  // copy instructions are opaque to the scheduler and would break up the MFMA / LDS-read interleave for nothing).
+  auto data_slice = [&](auto first_c, auto last_c, auto copier_c) {
+    constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value, COPIER = decltype(copier_c)::value;
     const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
-    // (a) this wave's copies of slice G+1 have landed once only slice G+2's four are outstanding
+    // (a) this wave's copies of slice G+1 have landed once only those of slice G+2 are outstanding
     if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
-    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 2)) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
-    // (c) refill the stage slice G-1 occupied with slice G+DIST.  The two waves that share a SIMD do this at
-    //     different points of the slice, so that one of them always has MFMAs to issue
-    if constexpr (EARLY) issue_one(G + DIST);
+    // (c) the copying waves refill the stage slice G-1 occupied with slice G+DIST, while the other wave of
+    //     their SIMD starts on the MFMAs of the slice
+    if constexpr (COPIER) issue_one(G + DIST);
     // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
     //     (the second one reads from slice G+1, which barrier (b) has certified)
     load_frags(st_cur, offA[1], offB[1], fa1, fb1);
     if constexpr (FIRST) mma_first(fa0, fb0); else mma_only(fa0, fb0);
     interleave_hint();
-    if constexpr (!EARLY) issue_one(G + DIST);
+    __builtin_amdgcn_sched_barrier(0);  // keep the two steps apart: each has its own interleave pattern
     load_frags(st_nxt, LAST ? offA_aug : offA[0], LAST ? offB_aug : offB[0], fa0, fb0);
     mma_only(fa1, fb1);
     interleave_hint();
@@ -620,7 +634,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 
   while (have) {
     // ---------------- the nsl >= 2 data slices of the tile
-    if (wm) {
+    if (copier) {
       data_slice(T_{}, F_{}, T_{});
       for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, T_{});
       data_slice(F_{}, T_{}, T_{});
@@ -632,7 +646,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     // ---------------- the augmentation slice: one step, then the filter
     {
       if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
-      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (DIST - 2)) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
       wg_barrier();
       issue_one(G + DIST);
       ++G;
