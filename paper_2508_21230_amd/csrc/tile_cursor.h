@@ -38,14 +38,13 @@ constexpr uint32_t EJ_SB = 16;      // tiles per super-block edge (one super-blo
 struct TileCursor {
   uint32_t xcd, wpx;     // this workgroup's XCD; workgroups per XCD
   uint32_t self, nsbA, nsbB, ntA, ntB;
-  uint64_t target;       // position of this workgroup's next tile in the XCD's list
-  uint64_t rank0;        // position of the first non-empty tile of the current super-block's rectangle
+  uint32_t rem;          // position of this workgroup's next tile, counted from the first tile of the current rectangle
   uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
-  uint32_t start, wpx_all;  // (row-major ablation only) first tile and stride of this workgroup
+  uint32_t start, stride;  // (row-major ablation only) first tile and stride of this workgroup
   // self_join: upper triangle of an nt x nt grid (nt_a == nt_b); otherwise the whole nt_a x nt_b grid
   EJ_HD void init(uint32_t block, uint32_t nblocks, uint32_t self_join, uint32_t nt_a, uint32_t nt_b) {
     start = block;
-    wpx_all = nblocks;
+    stride = 0;
     xcd = block % EJ_NUM_XCD;
     wpx = (nblocks - xcd + EJ_NUM_XCD - 1) / EJ_NUM_XCD;  // workgroups with this XCD id
     self = self_join;
@@ -53,23 +52,26 @@ struct TileCursor {
     ntB = nt_b;
     nsbA = (nt_a + EJ_SB - 1) / EJ_SB;
     nsbB = (nt_b + EJ_SB - 1) / EJ_SB;
-    target = block / EJ_NUM_XCD;
-    rank0 = 0;
+    rem = block / EJ_NUM_XCD;
     P = Q = sbi = 0;
+#ifdef EJOIN_ABL_ROWMAJOR_TILES
+    stride = nblocks;
+#endif
   }
-  // self-join: upper triangle (I <= J); two sets: the whole ntA x ntB grid
-  EJ_HD bool cell_ok(uint32_t I, uint32_t J) const { return self ? (I <= J && J < ntB) : (I < ntA && J < ntB); }
+  // Tiles of row r (0..7) of a rectangle on the diagonal of the self-join: columns lo .. cj-1, with
+  // lo = max(0, a + r - b), where a and b are the rectangle's row and column offsets in its super-block.
+  static EJ_HD uint32_t diag_row_first(uint32_t a, uint32_t b, uint32_t r) { return a + r > b ? a + r - b : 0u; }
   // next tile of this workgroup; false when the work is exhausted
   EJ_HD bool next(uint32_t& I, uint32_t& J) {
 #ifdef EJOIN_ABL_ROWMAJOR_TILES
     // tiles of the triangle (or grid) in row-major order, tile t to workgroup t % nblocks; P, Q hold the
-    // row and column of this workgroup's next tile, rank0 the stride
-    if (rank0 == 0) {  // first call
-      rank0 = (uint64_t)wpx_all;
+    // row and column of this workgroup's next tile
+    if (rem != 0xFFFFFFFFu) {  // first call
+      rem = 0xFFFFFFFFu;
       P = 0;
       Q = start;
     } else {
-      Q += (uint32_t)rank0;
+      Q += stride;
     }
     while (P < ntA && Q >= ntB) {
       Q -= ntB;
@@ -81,29 +83,51 @@ struct TileCursor {
     J = EJ_UNIFORM(Q);
     return true;
 #endif
+    // Everything here is uniform over the workgroup and meant to stay on the scalar unit: 32-bit counters,
+    // closed forms for the number of tiles of a rectangle, and real branches around the rare cases.
     while (P < nsbA) {
       const uint32_t xp = (xcd + sbi) & 7;
-      const uint32_t I0 = P * EJ_SB + (xp >> 2) * 8, J0 = Q * EJ_SB + (xp & 3) * 4;
-      // may the rectangle hold empty cells?
-      const bool special = self ? ((P == Q) || (J0 + 4 > ntB)) : ((I0 + 8 > ntA) || (J0 + 4 > ntB));
-      uint32_t v = 32;
-      if (special) {
+      const uint32_t a = (xp >> 2) * 8, b = (xp & 3) * 4;  // the rectangle's offsets inside its super-block
+      const uint32_t I0 = P * EJ_SB + a, J0 = Q * EJ_SB + b;
+      // columns of the rectangle inside the grid, and rows (in the self-join's off-diagonal super-blocks all 8)
+      const uint32_t cj = J0 >= ntB ? 0u : (ntB - J0 < 4u ? ntB - J0 : 4u);
+      const uint32_t ri = self ? 8u : (I0 >= ntA ? 0u : (ntA - I0 < 8u ? ntA - I0 : 8u));
+      const bool on_diag = self && P == Q;
+      uint32_t v = ri * cj;
+      if (on_diag) {  // one super-block in every row of the self-join
         v = 0;
-        for (uint32_t c = 0; c < 32; ++c) v += cell_ok(I0 + (c >> 2), J0 + (c & 3)) ? 1u : 0u;
-      }
-      if (target < rank0 + v) {
-        uint32_t q = (uint32_t)(target - rank0), c = q;
-        if (special) {
-          for (c = 0; c < 32; ++c)
-            if (cell_ok(I0 + (c >> 2), J0 + (c & 3)) && q-- == 0) break;
+        for (uint32_t r = 0; r < 8; ++r) {
+          const uint32_t lo = diag_row_first(a, b, r);
+          v += lo < cj ? cj - lo : 0u;
         }
-        // every lane computes the same values; say so to the compiler (they feed scalar operands)
-        I = EJ_UNIFORM(I0 + (c >> 2));
-        J = EJ_UNIFORM(J0 + (c & 3));
-        target += wpx;
+      }
+      if (rem < v) {
+        uint32_t r = 0, c = rem;
+        if (on_diag) {
+          for (; r < 8; ++r) {
+            const uint32_t lo = diag_row_first(a, b, r);
+            const uint32_t cnt = lo < cj ? cj - lo : 0u;
+            if (c < cnt) {
+              c += lo;
+              break;
+            }
+            c -= cnt;
+          }
+        } else if (cj == 4) {
+          r = rem >> 2;
+          c = rem & 3;
+        } else {  // ragged last column of rectangles
+          while (c >= cj) {
+            c -= cj;
+            ++r;
+          }
+        }
+        I = EJ_UNIFORM(I0 + r);
+        J = EJ_UNIFORM(J0 + c);
+        rem += wpx;
         return true;
       }
-      rank0 += v;
+      rem -= v;
       ++sbi;
       if (++Q == nsbB) {  // super-blocks row-major; the self-join starts each row on the diagonal
         ++P;
