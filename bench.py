@@ -25,7 +25,7 @@ PEAK_FP16_TFLOPS = 2500.0  # MI355X dense FP16 MFMA, published
 # Bytes k_join fetches into L2 from the memory side plus bytes it writes, per launch, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy of known size
 # (profiles/k_join_workload3_hbm_counters.txt).  Only measured for the default workload.
-MEASURED_TRAFFIC_BYTES = {(3, 16, "pairs"): 1.900e12}
+MEASURED_TRAFFIC_BYTES = {(3, 16, "pairs"): 1.888e12}
 
 
 def load_eps(workload: int, S: int) -> float:

@@ -3,7 +3,7 @@
 // Method (arXiv 2508.21230, Section 3.1): Step 1 norms s_i, Step 2 Gram products a_ij on the
 // matrix cores with FP16 inputs / FP32 accumulation, Step 3 dist^2 = s_i + s_j - 2 a_ij, then
 // the "<= epsilon" filter of Section 2.2.1.  The tiling below is designed for CDNA4 (64-wide
-// wavefronts, v_mfma_f32_32x32x16_f16, 160 KB LDS with 64 banks, 8 XCDs with private L2s); the
+// wavefronts, v_mfma_f32_16x16x32_f16, 160 KB LDS with 64 banks, 8 XCDs with private L2s); the
 // paper's A100 tiling (Section 3.2-3.3) is prior art, not the blueprint.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -56,16 +56,37 @@ static_assert(NSTAGE == 3 || NSTAGE == 4, "the slice pipeline reads one slice ah
 // Device status word written by k_aux, read by the other kernels.
 constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
 
-// LDS layout of a panel: row r (0..255) occupies bytes [r*64, r*64+64); its four 16-byte chunks
-// are stored permuted, chunk c at position c ^ ((r >> 2) & 3).  The LDS has 64 banks of 4 B and a
-// ds_read_b128 serves 16 lanes per clock; 16 consecutive rows at the same logical chunk then fall
-// into 16 distinct 16-byte bank groups (4 rows per 256 B bank line x 4 positions).  This is the
-// role the XOR swizzle of Section 3.3.5 (Eq. 2) plays on the A100's 32 banks.
+// LDS layout of a panel: 256 rows of 64 B, four 16-byte chunks each.  Two things decide where the
+// chunk of point r (0..255), coordinates 8 k .. 8 k + 7 (k = 0..3) of the slice, is stored:
+//   * A v_mfma_f32_16x16x32_f16 operand wants, in lane l, point l%16 of a group of 16 and chunk k = l/16.
+//     The LDS serves a ds_read_b128 16 lanes at a time, and which lanes go together is not simply
+//     "16 consecutive": reading rows l%16 at chunk l/16 costs two cycles per group (measured).  A read
+//     in which lane l takes row l%32 of a group of 32 and chunk l/32 is served without conflicts (measured),
+//     so the layout is made such that the MFMA operand IS such a read: points come in groups of 32,
+//     (point 16 h + x, chunk 2 u + v) of a group is stored in row 16 v + x, chunk 2 h + u.  Fragment
+//     t = 2 T + h (points 16 t .. 16 t + 15 of the panel) is then: lane l reads row 32 T + l%32,
+//     chunk 2 h + l/32.
+//   * Chunk c of row r is stored at position c ^ swz(r): 16 consecutive rows at the same chunk
+//     then fall into 16 distinct 16-byte bank groups (the LDS has 64 banks of 4 B; 4 rows per
+//     256 B bank line x 4 positions).  This is the role the XOR swizzle of Section 3.3.5 (Eq. 2)
+//     plays on the A100's 32 banks.
 #ifdef EJOIN_ABL_NOSWIZZLE
 __host__ __device__ __forceinline__ int swz(int) { return 0; }
 #else
 __host__ __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 #endif
+// Which point (same group of 32) and which chunk of its slice the 16 bytes at (row, position p) hold.
+__host__ __device__ __forceinline__ void stored_at(int64_t row, int p, int64_t& point, int& chunk) {
+  const int c = p ^ swz((int)(row & 255));
+  point = (row & ~(int64_t)31) | ((c >> 1) << 4) | (row & 15);
+  chunk = 2 * (c & 1) + (int)((row >> 4) & 1);
+}
+// The inverse: index of the 16-byte chunk (row * 4 + position) that holds (point, chunk).
+__host__ __device__ __forceinline__ int64_t place_of(int64_t point, int chunk) {
+  const int64_t row = (point & ~(int64_t)31) | ((int64_t)(chunk & 1) << 4) | (point & 15);
+  const int c = 2 * (int)((point >> 4) & 1) + (chunk >> 1);
+  return row * 4 + (c ^ swz((int)(row & 255)));
+}
 
 struct JoinArgs {
   // "points" (rows of the distance matrix) and "query points" (columns); the self-join passes the same set twice
@@ -116,37 +137,34 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
   if (i < n) p[i] = v;
 }
 
-// Step 1 (Section 3.1): s_i = sum_k x_ik^2.  One wavefront per 32 consecutive points; the 32 x 32
+// Step 1 (Section 3.1): s_i = sum_k x_ik^2.  One wavefront per 16 consecutive points; the 16 x 16
 // Gram block of those points is accumulated with the same MFMA steps, in the same k order, as
 // the join kernel uses, and its diagonal is stored.  That makes s_i bit-identical to a_ii, and
 // to a_ij for a duplicate j of i, so duplicates come out at distance exactly 0.  (The paper
 // matches its norm rounding to its tensor cores' for the same reason.)  Also tracks max_i s_i
 // (as FP32 bits; s >= 0 so unsigned order is numeric order, and NaN/Inf sort above every finite value).
-__global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t ld, int k16steps,
+__global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t ld, int k32steps,
                                                float* __restrict__ s, uint32_t* __restrict__ max_bits) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t row0 = blk * 32;
+  const int64_t row0 = blk * 16;
   if (row0 >= n) return;
-  int64_t row = row0 + (lane & 31);
+  int64_t row = row0 + (lane & 15);
   if (row >= n) row = n - 1;
-  const half8* p = reinterpret_cast<const half8*>(X + row * ld) + (lane >> 5);
-  float16v acc;
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  for (int k = 0; k < k16steps; ++k) {
-    half8 a = p[2 * k];
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, a, acc, 0, 0, 0);
+  const half8* p = reinterpret_cast<const half8*>(X + row * ld) + (lane >> 4);
+  float4v acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < k32steps; ++k) {
+    half8 a = p[4 * k];
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, a, acc, 0, 0, 0);
   }
-  // element (row, col) of the 32x32 block sits in lane (col + 32*hi), register r with
-  // row = 8*(r/4) + 4*hi + r%4 ; the diagonal element of column c is in the lane whose
-  // hi equals bit 2 of c, register 4*(c/8) + c%4.
-  const int c = lane & 31, hi = lane >> 5;
+  // element (row, col) of the 16 x 16 block sits in lane col + 16 * (row / 4), register row % 4
+  const int c = lane & 15, g = lane >> 4;
   uint32_t bits = 0;
-  if (((c >> 2) & 1) == hi && row0 + c < n) {
-    const int want = 4 * (c >> 3) + (c & 3);
+  if ((c >> 2) == g && row0 + c < n) {
+    const int want = c & 3;
     float v = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
+    for (int r = 0; r < 4; ++r)
       if (r == want) v = acc[r];
     s[row0 + c] = v;
     bits = __float_as_uint(v);
@@ -161,15 +179,13 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   }
 }
 
-// Rows past the end of the data set use this augmentation row: -60000 c in place of -s/2 (at least
-// the largest norm of the data), so that none of their pairs passes the filter for any ordinary
-// epsilon (the rare path masks them exactly) and nothing non-finite enters the matrix cores.
-__device__ __forceinline__ uint4 aux_row_out_of_range(uint32_t cbits) {
-  return make_uint4(0xFB53u /* -60000 in FP16 */, 0u, cbits | (cbits << 16), cbits);
-}
+// Rows past the end of the data set carry -60000 c in place of -s/2 (at least the largest norm of the
+// data), so that none of their pairs passes the filter for any ordinary epsilon (the rare path masks
+// them exactly) and nothing non-finite enters the matrix cores.
+constexpr uint32_t P1_OUT_OF_RANGE = 0xFB53u;  // -60000 in FP16
 
 // Augmentation rows.  Step 3 of Section 3.1 (dist^2 = s_i + s_j - 2 a_ij) is folded into the
-// matrix-core accumulation: after the d/16 Gram steps one more 16-wide MFMA step adds
+// matrix-core accumulation: after the Gram steps one more 16-wide MFMA step adds
 // -s_i/2 - s_j/2 to a_ij, so the accumulator ends as acc' = -dist^2 / 2 and the filter becomes a
 // sign-like test against -eps^2/2.  -s/2 is FP32; scaled by 2^-m it is split into three FP16 pieces
 // p1 + p2 + p3, where m puts the largest norm of the data just below 2^16 (s_max / 2 < 2^15 2^m),
@@ -177,14 +193,16 @@ __device__ __forceinline__ uint4 aux_row_out_of_range(uint32_t cbits) {
 // of a step by their exponent fields; a subnormal c would cost them low bits).  The split is exact
 // for every point with s >= max(2^-16 s_max, 2^-14): the 24 mantissa bits of s / 2^(m+1) then lie
 // above FP16's smallest subnormal.  A smaller norm is carried to 2^-25 2^m absolute.  Point i's
-// 16-byte row is  H_i = { p1, p2, p3, 0, c, c, c, 0 }.  As the A operand of the extra
-// step a row is used as is (k = 0..7; k = 8..15 are zero), as the B operand its two halves are
-// swapped, { c, c, c, 0, q1, q2, q3, 0 }, so that  A_i . B_j = c (p1+p2+p3)_i + c (q1+q2+q3)_j
-// = -s_i/2 - s_j/2  (every product is exact in FP32).
-// H (npad rows) serves the dense-tile kernel.  For the join the rows are also written as one more
-// k-block behind the packed X (`aug`, may be null): row r = { chunk 0: H_r, chunk 1: H_r with halves
-// swapped, chunks 2 and 3: zero }, chunk c at position c ^ swz(r) like every other block, so that the
-// join kernel streams the augmentation step through the same LDS stages as the data.
+// 16-byte row is  H_i = { P_i, C } = { p1, p2, p3, 0, c, c, c, 0 }; the extra step multiplies
+// pieces by constants, c (p1 + p2 + p3)_i + c (q1 + q2 + q3)_j = -s_i/2 - s_j/2, every product exact in FP32.
+// H (npad rows) serves the dense-tile kernel.  For the join the operands of the extra step are also
+// written, ready made, as one more k-block behind the packed X (`aug`, may be null), so that the join
+// kernel streams them through the same LDS stages as the data.  Row r of that block, with m = r % 32
+// and b = r - m the first row of its group of 32 (see the augmentation step of k_join for the why):
+//   chunk 0 = { P_x, P_y }, x = b + 16 (m/16) + 8 ((m/4)%2) + m%4, y = x + 4   (A operand, k = 0..7, of row m)
+//   chunk 1 = { P_x, P_y }, x = b + m%16, y = x + 16                            (B operand, k = 8..15, of column m)
+//   chunk 2 = { C, 0 },  chunk 3 = { 0, C }                                     (the indicator halves)
+// chunk c at position c ^ swz(r) like every other block.
 __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max,
                       uint4* __restrict__ H, uint4* __restrict__ aug) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -201,31 +219,39 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
   auto bits = [](_Float16 x) { return (uint32_t)__builtin_bit_cast(uint16_t, x); };
   if (i == 0) status_and_max[0] = st;
   if (i >= npad) return;
-  uint4 h = make_uint4(0, 0, 0, 0);
-  if (i >= n) h = aux_row_out_of_range(bits(c));
-  else if (st == ST_OK) {
-    const float v = ldexpf(-0.5f * s[i], -m);
+  // the pieces of point x as two 32-bit words { p1 | p2 << 16, p3 }
+  auto pieces = [&](int64_t x) -> uint2 {
+    if (x >= n) return make_uint2(P1_OUT_OF_RANGE, 0u);
+    if (st != ST_OK) return make_uint2(0u, 0u);
+    const float v = ldexpf(-0.5f * s[x], -m);
     const _Float16 p1 = (_Float16)v;
     const float r1 = v - (float)p1;
     const _Float16 p2 = (_Float16)r1;
     const _Float16 p3 = (_Float16)(r1 - (float)p2);
-    h.x = bits(p1) | (bits(p2) << 16);
-    h.y = bits(p3);
-    h.z = bits(c) | (bits(c) << 16);
-    h.w = bits(c);
-  }
-  H[i] = h;
+    return make_uint2(bits(p1) | (bits(p2) << 16), bits(p3));
+  };
+  const uint2 cc = (i >= n || st == ST_OK) ? make_uint2(bits(c) | (bits(c) << 16), bits(c)) : make_uint2(0u, 0u);
+  const uint2 own = pieces(i);
+  H[i] = make_uint4(own.x, own.y, cc.x, cc.y);
   if (aug) {
     const int sw = swz((int)(i & 255));
+    const int r = (int)(i & 31);
+    const int64_t b = i - r;
+    const int64_t xa = b + 16 * (r >> 4) + 8 * ((r >> 2) & 1) + (r & 3), xb = b + (r & 15);
+    const uint2 a0 = pieces(xa), a1 = pieces(xa + 4), b0 = pieces(xb), b1 = pieces(xb + 16);
     uint4* row = aug + i * 4;
-    row[0 ^ sw] = h;
-    row[1 ^ sw] = make_uint4(h.z, h.w, h.x, h.y);
-    row[2 ^ sw] = make_uint4(0, 0, 0, 0);
-    row[3 ^ sw] = make_uint4(0, 0, 0, 0);
+    row[0 ^ sw] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+    row[1 ^ sw] = make_uint4(b0.x, b0.y, b1.x, b1.y);
+    row[2 ^ sw] = make_uint4(cc.x, cc.y, 0u, 0u);
+    row[3 ^ sw] = make_uint4(0u, 0u, cc.x, cc.y);
   }
 }
 
 __device__ __forceinline__ half8 as_half8(uint4 v) { return __builtin_bit_cast(half8, v); }
+__device__ __forceinline__ float16v cat4(float4v a, float4v b, float4v c, float4v d) {
+  return __builtin_shufflevector(__builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7), __builtin_shufflevector(c, d, 0, 1, 2, 3, 4, 5, 6, 7),
+                                 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+}
 
 // Ingestion: FP32 rows -> FP16 rows in the layout the join expects (row stride ld16, a multiple of 64,
 // columns d .. ld16-1 zero).  y = fp16_rne(fl32(scale * fl32(x - center_k))).  One thread per 8 output columns.
@@ -252,12 +278,12 @@ __global__ void k_convert_f32(const float* __restrict__ X32, int64_t n, int32_t 
 }
 
 // Packed copy of X for the join kernel.  Xp is cut into k-blocks of 32 coordinates; block kb holds,
-// for every row r < npad, the row's four 16-byte chunks of that block, already permuted the way
-// the LDS wants them (chunk c at position c ^ swz(r)); rows n .. npad-1 are zero.  In this layout a
-// 256-row panel of one k-block is 16 KB of contiguous memory, so the global->LDS copies are straight
-// 1 KB block copies made of full 128-byte lines (in the row-major X a 32-coordinate slice of a row is
-// half a line, and the L2 would be asked for every line twice).
-// Thread t writes chunk t of Xp (fully coalesced writes; reads are 64-byte segments).
+// for every row r < npad, the 64 bytes of a row of the LDS panel, already arranged the way the LDS wants
+// them (see stored_at); points n .. npad-1 are zero.  In this layout a 256-row panel of one k-block is
+// 16 KB of contiguous memory, so the global->LDS copies are straight 1 KB block copies made of full
+// 128-byte lines (in the row-major X a 32-coordinate slice of a row is half a line, and the L2 would be
+// asked for every line twice).
+// Thread t writes chunk t of Xp (fully coalesced writes; reads are 16-byte pieces).
 __global__ void k_pack(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int nkb, uint4* __restrict__ Xp) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = (int64_t)nkb * npad * 4;
@@ -265,8 +291,11 @@ __global__ void k_pack(const uint16_t* __restrict__ X, int64_t n, int64_t npad, 
   const int p = (int)(t & 3);
   const int64_t rk = t >> 2;
   const int64_t kb = rk / npad, r = rk - kb * npad;
+  int64_t point;
+  int chunk;
+  stored_at(r, p, point, chunk);
   uint4 v = make_uint4(0, 0, 0, 0);
-  if (r < n) v = *reinterpret_cast<const uint4*>(X + r * ld + kb * KSLICE + ((p ^ swz((int)(r & 255))) << 3));
+  if (point < n) v = *reinterpret_cast<const uint4*>(X + point * ld + kb * KSLICE + (chunk << 3));
   Xp[t] = v;
 }
 
@@ -286,11 +315,14 @@ __global__ void k_split_pack(const float* __restrict__ X32, int64_t n, int64_t n
   const int p = (int)(t & 3);
   const int64_t rk = t >> 2;
   const int64_t kb = rk / npad, r = rk - kb * npad;
-  const int k0 = (int)kb * KSLICE + ((p ^ swz((int)(r & 255))) << 3);  // first coordinate of the chunk stored at position p
+  int64_t point;
+  int chunk;
+  stored_at(r, p, point, chunk);
+  const int k0 = (int)kb * KSLICE + (chunk << 3);  // first coordinate of the chunk stored here
   half8 hi, lo;
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    const float x = (r < n && k0 + k < d) ? X32[r * ld32 + k0 + k] : 0.f;
+    const float x = (point < n && k0 + k < d) ? X32[point * ld32 + k0 + k] : 0.f;
     const _Float16 h = (_Float16)x;
     float rest = x - (float)h;
     asm volatile("" : "+v"(rest));  // the residual is an FP32 number: no fused subtract-convert
@@ -308,35 +340,29 @@ __global__ void k_split_pack(const float* __restrict__ X32, int64_t n, int64_t n
 }
 
 // Norms for the split variant: s_i = A'_i . B'_i, accumulated by the same MFMA steps in the same
-// order as the join kernel accumulates a_ii (k-blocks in order, two 16-wide steps per block), read
-// from the packed arrays.  One wavefront per 32 consecutive points, like k_norms.
+// order as the join kernel accumulates a_ii (k-blocks in order, one 32-wide step per block), read
+// from the packed arrays.  One wavefront per 16 consecutive points, like k_norms.
 __global__ __launch_bounds__(256) void k_norms_packed(const uint4* __restrict__ XpA, const uint4* __restrict__ XpB, int64_t n,
                                                       int64_t npad, int nkb_total, float* __restrict__ s,
                                                       uint32_t* __restrict__ max_bits) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t row0 = blk * 32;
+  const int64_t row0 = blk * 16;
   if (row0 >= n) return;
-  const int64_t row = row0 + (lane & 31);  // < npad: rows past n are zero
-  const int hi = lane >> 5, sw = swz((int)(row & 255));
-  float16v acc;
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const int g = lane >> 4;
+  const int64_t at = place_of(row0 + (lane & 15), g);  // (< npad: points past n are zero)
+  float4v acc = {0.f, 0.f, 0.f, 0.f};
   for (int kb = 0; kb < nkb_total; ++kb) {
-    const uint4* ra = XpA + ((int64_t)kb * npad + row) * 4;
-    const uint4* rb = XpB + ((int64_t)kb * npad + row) * 4;
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int pos = (2 * t + hi) ^ sw;
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ra[pos]), as_half8(rb[pos]), acc, 0, 0, 0);
-    }
+    const int64_t off = (int64_t)kb * npad * 4 + at;
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(XpA[off]), as_half8(XpB[off]), acc, 0, 0, 0);
   }
-  const int c = lane & 31;
+  const int c = lane & 15;
   uint32_t bits = 0;
-  if (((c >> 2) & 1) == hi && row0 + c < n) {
-    const int want = 4 * (c >> 3) + (c & 3);
+  if ((c >> 2) == g && row0 + c < n) {
+    const int want = c & 3;
     float v = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
+    for (int r = 0; r < 4; ++r)
       if (r == want) v = acc[r];
     s[row0 + c] = v;
     bits = v < 0.f ? 0u : __float_as_uint(v);  // (a sum that rounds below zero counts as zero; NaN stays NaN)
@@ -346,35 +372,55 @@ __global__ __launch_bounds__(256) void k_norms_packed(const uint4* __restrict__ 
   if (lane == 0) atomicMax(max_bits, bits);
 }
 
-// Dense block of squared distances with the join's arithmetic: one wavefront per 32 x 32 block.
+// Dense block of squared distances with the join's arithmetic: one wavefront per 32 x 32 region, computed
+// the way the join kernel computes a region of its wave tile: four 16 x 16 blocks accumulated with
+// v_mfma_f32_16x16x32_f16, then one v_mfma_f32_32x32x16_f16 on the four blocks' registers side by side that
+// adds -s_i/2 - s_j/2 (operand layout: see the augmentation step of k_join).
 __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ X, const uint4* __restrict__ H,
-                                                  const uint32_t* __restrict__ status, int64_t n, int64_t ld, int k16steps,
+                                                  const uint32_t* __restrict__ status, int64_t n, int64_t ld, int k32steps,
                                                   int64_t i0, int64_t j0, int rows, int cols, float* __restrict__ out) {
   if (*status != ST_OK) return;
   const int lane = threadIdx.x & 63;
   const int bi = blockIdx.y * 32, bj = blockIdx.x * 32;
-  int64_t ra = i0 + bi + (lane & 31), rb = j0 + bj + (lane & 31);
-  if (ra >= n) ra = n - 1;
-  if (rb >= n) rb = n - 1;
-  const half8* pa = reinterpret_cast<const half8*>(X + ra * ld) + (lane >> 5);
-  const half8* pb = reinterpret_cast<const half8*>(X + rb * ld) + (lane >> 5);
-  float16v acc;
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  for (int k = 0; k < k16steps; ++k) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(pa[2 * k], pb[2 * k], acc, 0, 0, 0);
-  uint4 ha = make_uint4(0, 0, 0, 0), hb = ha;
-  if (lane < 32) {
-    ha = H[ra];
-    const uint4 t = H[rb];
-    hb = make_uint4(t.z, t.w, t.x, t.y);
+  const int r16 = lane & 15, g = lane >> 4;
+  auto row_a = [&](int local) { const int64_t r = i0 + bi + local; return r >= n ? n - 1 : r; };
+  auto row_b = [&](int local) { const int64_t r = j0 + bj + local; return r >= n ? n - 1 : r; };
+  const half8* pa0 = reinterpret_cast<const half8*>(X + row_a(r16) * ld) + g;
+  const half8* pa1 = reinterpret_cast<const half8*>(X + row_a(16 + r16) * ld) + g;
+  const half8* pb0 = reinterpret_cast<const half8*>(X + row_b(r16) * ld) + g;
+  const half8* pb1 = reinterpret_cast<const half8*>(X + row_b(16 + r16) * ld) + g;
+  float4v acc[2][2];
+  for (int a = 0; a < 2; ++a)
+    for (int c = 0; c < 2; ++c) acc[a][c] = float4v{0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < k32steps; ++k) {
+    const half8 a0 = pa0[4 * k], a1 = pa1[4 * k], b0 = pb0[4 * k], b1 = pb1[4 * k];
+    acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[1][1], 0, 0, 0);
   }
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ha), as_half8(hb), acc, 0, 0, 0);
-  const int c = bj + (lane & 31), hi = lane >> 5;
-  if (c < cols) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int rr = bi + 8 * (r >> 2) + 4 * hi + (r & 3);
-      if (rr < rows) out[(int64_t)rr * cols + c] = (i0 + rr == j0 + c) ? 0.f : fmaxf(-2.f * acc[r], 0.f);
+  // augmentation operands: H_x = { p1, p2, p3, 0, c, c, c, 0 } (16 bytes): pieces in .x .y, constant in .z .w
+  const int m = lane & 31, upper = lane >> 5;
+  uint4 ha, hb;
+  {
+    const int ra = 16 * (m >> 4) + 8 * ((m >> 2) & 1) + (m & 3);
+    const uint4 h0 = H[row_a(ra)], h1 = H[row_a(ra + 4)];
+    const uint4 q0 = H[row_b(m & 15)], q1 = H[row_b(16 + (m & 15))];
+    const int qc = (m >> 3) & 1, g0 = m >> 4;
+    if (!upper) {
+      ha = make_uint4(h0.x, h0.y, h1.x, h1.y);
+      hb = g0 ? make_uint4(0, 0, q0.z, q0.w) : make_uint4(q0.z, q0.w, 0, 0);
+    } else {
+      ha = qc ? make_uint4(0, 0, h0.z, h0.w) : make_uint4(h0.z, h0.w, 0, 0);
+      hb = make_uint4(q0.x, q0.y, q1.x, q1.y);
     }
+  }
+  const float16v res = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ha), as_half8(hb), cat4(acc[0][0], acc[0][1], acc[1][0], acc[1][1]), 0, 0, 0);
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int rr = bi + 16 * (q >> 3) + 4 * g + (q & 3);
+    const int cc = bj + 16 * ((q >> 2) & 1) + r16;
+    if (rr < rows && cc < cols) out[(int64_t)rr * cols + cc] = (i0 + rr == j0 + cc) ? 0.f : fmaxf(-2.f * res[q], 0.f);
   }
 }
 
@@ -427,7 +473,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
-  const int r32 = lane & 31, hi = lane >> 5;
+  const int r16 = lane & 15, g = lane >> 4;
   const int nsl = a.nslices;       // data slices per tile
   const int nslT = nsl + 1;        // plus the augmentation slice (nslT >= DIST: nsl >= 2 because d is padded to 64)
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
@@ -457,56 +503,62 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   };
   constexpr int NCOPY = 8;  // copy instructions per slice and copying wave
 
-  // --- fragment read addressing (byte offsets inside a stage).  A operand of
-  // v_mfma_f32_32x32x16_f16: lane l supplies row l%32, coordinates 8*(l/32) .. +7 of the 16-wide step.
-  // m-tile / n-tile t adds 32 rows = 2048 B (swz unchanged: 32 rows = 8 groups of 4).
-  // In the augmentation slice the A operand reads chunk 0 (lanes 32..63: chunk 2 = zeros) and the
-  // B operand chunk 1 (chunk 3).
-  uint32_t offA[2], offB[2], offB_aug;
+  // --- fragment read addressing (byte offsets inside a stage).  Operands of v_mfma_f32_16x16x32_f16:
+  // lane l supplies point l%16 of the fragment, coordinates 8*(l/16) .. +7 of the 32-wide step; in the
+  // panel layout (see stored_at) that is row l%32 of the fragment's group of 32 rows, chunk 2 h + l/32
+  // for fragment t = 2 T + h.  Group T adds 32 rows = 2048 B (swz unchanged: 32 rows = 8 groups of 4).
+  uint32_t offA[2], offB[2];
   {
-    const int rowA = wm * 128 + r32, rowB = wn * 64 + r32;
+    const int rowA = wm * 128 + (lane & 31), rowB = wn * 64 + (lane & 31);
 #pragma unroll
-    for (int k16 = 0; k16 < 2; ++k16) {
-      offA[k16] = lds0 + rowA * 64 + (((2 * k16 + hi) ^ swz(rowA)) << 4);
-      offB[k16] = lds0 + PANEL_BYTES + rowB * 64 + (((2 * k16 + hi) ^ swz(rowB)) << 4);
+    for (int h = 0; h < 2; ++h) {
+      offA[h] = lds0 + rowA * 64 + (((2 * h + (lane >> 5)) ^ swz(rowA)) << 4);
+      offB[h] = lds0 + PANEL_BYTES + rowB * 64 + (((2 * h + (lane >> 5)) ^ swz(rowB)) << 4);
     }
-    offB_aug = lds0 + PANEL_BYTES + rowB * 64 + (((1 + 2 * hi) ^ swz(rowB)) << 4);
   }
-  const uint32_t offA_aug = lds0 + (wm * 128 + r32) * 64 + (((2 * hi) ^ swz(wm * 128 + r32)) << 4);
-  auto load_frags = [&](uint32_t stage_off, uint32_t oa, uint32_t ob, half8 (&fa)[4], half8 (&fb)[2]) {
-    const __attribute__((address_space(3))) char* pa = (const __attribute__((address_space(3))) char*)(uintptr_t)(oa + stage_off);
-    const __attribute__((address_space(3))) char* pb = (const __attribute__((address_space(3))) char*)(uintptr_t)(ob + stage_off);
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const __attribute__((address_space(3))) half8*>(pa + mt * 2048);
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) fb[nt] = *reinterpret_cast<const __attribute__((address_space(3))) half8*>(pb + nt * 2048);
+  // Operands of the augmentation step (one v_mfma_f32_32x32x16_f16 per 32 x 32 region, see there): lane l
+  // supplies row (or column) m = l%32 of the region, k = 8*(l/32) .. +7, and finds its 16 bytes ready made in
+  // the augmentation slice (layout: k_aux): the A operand in chunk 0 of row m (k = 0..7) or, for k = 8..15,
+  // the indicator of bit 3 of m (chunk 2 or 3 of any row); the B operand the indicator of bit 4 of m
+  // (k = 0..7) or chunk 1 of column m (k = 8..15).  Region t of a panel adds 32 rows = 2048 B.
+  uint32_t offA_aug, offB_aug;
+  {
+    const int m = lane & 31, upper = lane >> 5;
+    const int rowA = wm * 128 + m, rowB = wn * 64 + m;
+    const int chunkA = upper ? 2 + ((m >> 3) & 1) : 0;
+    const int chunkB = upper ? 1 : 2 + (m >> 4);
+    offA_aug = lds0 + rowA * 64 + ((chunkA ^ swz(rowA)) << 4);
+    offB_aug = lds0 + PANEL_BYTES + rowB * 64 + ((chunkB ^ swz(rowB)) << 4);
+  }
+  typedef const __attribute__((address_space(3))) char* lds_cptr;
+  typedef const __attribute__((address_space(3))) half8* lds_h8ptr;
+  // fragment t (points 16 t .. 16 t + 15 of the wave tile's rows or columns); off: offA or offB (+ stage offset)
+  auto frag = [&](uint32_t stage_off, const uint32_t (&off)[2], int t) -> half8 {
+    return *reinterpret_cast<lds_h8ptr>((lds_cptr)(uintptr_t)(off[t & 1] + stage_off) + (t >> 1) * 2048);
   };
+  // augmentation operand of region t (points 32 t .. 32 t + 31); addr: offA_aug or offB_aug + stage offset
+  auto aug_operand = [&](uint32_t addr, int t) -> half8 { return *reinterpret_cast<lds_h8ptr>((lds_cptr)(uintptr_t)addr + t * 2048); };
 
-  float16v acc[4][2];
-  // One 16-wide step: the eight MFMAs of the wave tile.  The scheduling hints spread the LDS reads of
-  // the following step's fragments between the first MFMAs, so that they complete under the rest.
-  auto mma_only = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
+  // acc[mt][nt]: the 16 x 16 block at rows 16 mt, columns 16 nt of the wave tile
+  float4v acc[8][4];
+  // Four MFMAs: column block nt of half H of the wave tile (rows 64 H .. 64 H + 63); they share their B
+  // operand.  (The 16x16x32 shape accumulates 32 products per accumulator access, against 16 for 32x32x16:
+  // on operands that toggle, the chip's power limit allows it a 14 % higher rate.)
+  auto mma4 = [&](auto first_c, auto h_c, auto nt_c, const half8 (&fa)[4], const half8& b) {
+    constexpr bool FIRST = decltype(first_c)::value;
+    constexpr int H = decltype(h_c)::value, NT = decltype(nt_c)::value;
+    const float4v z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
-  };
-  auto mma_first = [&](const half8 (&fa)[4], const half8 (&fb)[2]) {
-    float16v z;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[mt], fb[nt], z, 0, 0, 0);
-  };
-  auto interleave_hint = [&]() {
-#pragma unroll
-    for (int i = 0; i < 6; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+    for (int u = 0; u < 4; ++u) {
+      const int t = (NT & 1) ? 3 - u : u;  // up, down, up, down: only one operand changes from one MFMA to the next
+      acc[4 * H + t][NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[t], b, FIRST ? z : acc[4 * H + t][NT], 0, 0, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  };
+  // scheduling hints: `reads` LDS reads, then four MFMAs
+  auto hint = [&](auto reads_c) {
+    constexpr int R = decltype(reads_c)::value;
+    if constexpr (R > 0) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
   };
 
   // --- per-wave result staging (pair mode): entries are appended in LDS and written out in bulk
@@ -600,15 +652,83 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // outstanding (the waves that do not copy have nothing outstanding: their waits pass at once)
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 1)) : "memory");
   __syncthreads();
-  half8 fa0[4], fb0[2], fa1[4], fb1[2];
-  load_frags(0, offA[0], offB[0], fa0, fb0);
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  using I0_ = std::integral_constant<int, 0>;
+  using I1_ = std::integral_constant<int, 1>;
+  using I2_ = std::integral_constant<int, 2>;
+  using I3_ = std::integral_constant<int, 3>;
+  // Fragment registers: the A fragments of the two halves of the wave tile and the four B fragments.  A slice
+  // starts with faL and fb[0..2] in registers (read under the slice before); fb[3] and faH follow under its first half.
+  half8 faL[4], faH[4], fb[4];
+  auto load_first = [&](uint32_t stage_off) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) faL[t] = frag(stage_off, offA, t);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) fb[t] = frag(stage_off, offB, t);
+  };
+  load_first(0);
 
-  // One data slice (G-th of the stream).  FIRST: first slice of a tile (accumulators start from zero);
-  // LAST: last data slice of a tile (the fragments read ahead are those of the augmentation slice).
-  // COPIER: the instance the copying waves run; the other waves run one without any copy code in it (the
-  // copy instructions are opaque to the scheduler and would break up the MFMA / LDS-read interleave for nothing).
+  // One slice (G-th of the stream) = one 32-wide step: 32 MFMAs, upper half of the wave tile then lower half, each
+  // column block by column block.  A B fragment is dead after its four MFMAs of the lower half, and the fragment of
+  // the next slice is read into its place right away; the A fragments of the upper half are re-read under the lower
+  // half.  FIRST: first slice of a tile (accumulators start from zero).  oa, ob: lane addresses of this slice's
+  // fragments, oa_n, ob_n: of the next slice's, which the barrier of this slice has certified.
+  auto mma_slice = [&](auto first_c, auto last_c, uint32_t st_cur, uint32_t st_nxt) {
+    constexpr bool LAST = decltype(last_c)::value;
+    fb[3] = frag(st_cur, offB, 3);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) faH[t] = frag(st_cur, offA, 4 + t);
+    mma4(first_c, I0_{}, I0_{}, faL, fb[0]);
+    mma4(first_c, I0_{}, I1_{}, faL, fb[1]);
+    mma4(first_c, I0_{}, I2_{}, faL, fb[2]);
+    mma4(first_c, I0_{}, I3_{}, faL, fb[3]);
+    hint(I2_{});
+    hint(I1_{});
+    hint(I1_{});
+    hint(I1_{});
+    __builtin_amdgcn_sched_barrier(0);  // keep the two halves apart: each has its own interleave pattern
+    if constexpr (!LAST) {
+      faL[0] = frag(st_nxt, offA, 0);
+      faL[1] = frag(st_nxt, offA, 1);
+      mma4(first_c, I1_{}, I0_{}, faH, fb[0]);
+      fb[0] = frag(st_nxt, offB, 0);
+      faL[2] = frag(st_nxt, offA, 2);
+      mma4(first_c, I1_{}, I1_{}, faH, fb[1]);
+      fb[1] = frag(st_nxt, offB, 1);
+      faL[3] = frag(st_nxt, offA, 3);
+      mma4(first_c, I1_{}, I2_{}, faH, fb[2]);
+      fb[2] = frag(st_nxt, offB, 2);
+      mma4(first_c, I1_{}, I3_{}, faH, fb[3]);
+      hint(I2_{});
+      hint(I2_{});
+      hint(I2_{});
+      hint(I1_{});
+    } else {
+      // the slice that follows is the augmentation slice: its six operands go where the fragments would
+      // (faL[t]: A operand of region t, fb[0], fb[1]: B operands)
+      const uint32_t oa_n = st_nxt + offA_aug, ob_n = st_nxt + offB_aug;
+      faL[0] = aug_operand(oa_n, 0);
+      faL[1] = aug_operand(oa_n, 1);
+      mma4(first_c, I1_{}, I0_{}, faH, fb[0]);
+      fb[0] = aug_operand(ob_n, 0);
+      faL[2] = aug_operand(oa_n, 2);
+      mma4(first_c, I1_{}, I1_{}, faH, fb[1]);
+      fb[1] = aug_operand(ob_n, 1);
+      faL[3] = aug_operand(oa_n, 3);
+      mma4(first_c, I1_{}, I2_{}, faH, fb[2]);
+      mma4(first_c, I1_{}, I3_{}, faH, fb[3]);
+      hint(I2_{});
+      hint(I2_{});
+      hint(I2_{});
+      hint(I0_{});
+    }
+  };
+  // One data slice.  LAST: last data slice of a tile (the fragments read ahead are those of the augmentation
+  // slice).  COPIER: the instance the copying waves run; the other waves run one without any copy code in it
+  // (the copy instructions are opaque to the scheduler and would break up the MFMA / LDS-read interleave for nothing).
   auto data_slice = [&](auto first_c, auto last_c, auto copier_c) {
-    constexpr bool FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value, COPIER = decltype(copier_c)::value;
+    constexpr bool COPIER = decltype(copier_c)::value;
     const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
     // (a) this wave's copies of slice G+1 have landed once only those of slice G+2 are outstanding
     if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
@@ -618,19 +738,10 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     // (c) the copying waves refill the stage slice G-1 occupied with slice G+DIST, while the other wave of
     //     their SIMD starts on the MFMAs of the slice
     if constexpr (COPIER) issue_one(G + DIST);
-    // (d) slice G: two 16-wide steps, each overlapped with the LDS reads of the step after it
-    //     (the second one reads from slice G+1, which barrier (b) has certified)
-    load_frags(st_cur, offA[1], offB[1], fa1, fb1);
-    if constexpr (FIRST) mma_first(fa0, fb0); else mma_only(fa0, fb0);
-    interleave_hint();
-    __builtin_amdgcn_sched_barrier(0);  // keep the two steps apart: each has its own interleave pattern
-    load_frags(st_nxt, LAST ? offA_aug : offA[0], LAST ? offB_aug : offB[0], fa0, fb0);
-    mma_only(fa1, fb1);
-    interleave_hint();
+    // (d) the MFMAs of slice G, overlapped with the LDS reads of what follows
+    mma_slice(first_c, last_c, st_cur, st_nxt);
     ++G;
   };
-  using T_ = std::true_type;
-  using F_ = std::false_type;
 
   while (have) {
     // ---------------- the nsl >= 2 data slices of the tile
@@ -643,38 +754,56 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, F_{});
       data_slice(F_{}, T_{}, F_{});
     }
-    // ---------------- the augmentation slice: one step, then the filter
+    // ---------------- the augmentation slice: one step, then the filter.
+    // The step adds -s_i/2 - s_j/2 to every accumulator with eight v_mfma_f32_32x32x16_f16, one per 32 x 32
+    // region of the wave tile, half the matrix-core time that 32 more 16x16x32 (with 26 of 32 products zero)
+    // would take.  A region's accumulator is its four 16 x 16 blocks' registers side by side, R = (mt2, nt2):
+    // register q = 8 a + 4 c + r of lane l holds the pair  i = 16 a + 4 (l/16) + r,  j = 16 c + l%16  of the
+    // region, where the 32 x 32 MFMA puts its element  m = 8 (q/4) + 4 (l/32) + q%4,  n = l%32.  So the step
+    // needs  D[m][n] = -s_i/2 - s_j/2  with  i = i(m; bit 4 of n),  j = j(n%16; bit 3 of m),  which is bilinear
+    // in indicator columns:  row m of the A operand = { P(i(m;0)), P(i(m;1)), c [bit3(m)=0], c [bit3(m)=1] },
+    // row n of the B operand = { c [bit4(n)=0], c [bit4(n)=1], P(j(n;0)), P(j(n;1)) }, where P(x) = {p1, p2, p3, 0}
+    // are the pieces of -s_x/2 and c stands for {c, c, c, 0}.  Of the 16 products of an element 6 are non-zero
+    // and each is exact, as in a plain { P, c } . { c, P } step.
+    float16v R[4][2];
     {
       if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
       else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
       wg_barrier();
       issue_one(G + DIST);
       ++G;
-      mma_only(fa0, fb0);
+#pragma unroll
+      for (int mt2 = 0; mt2 < 4; ++mt2)
+#pragma unroll
+        for (int nt2 = 0; nt2 < 2; ++nt2)
+          R[mt2][nt2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+              faL[mt2], fb[nt2], cat4(acc[2 * mt2][2 * nt2], acc[2 * mt2][2 * nt2 + 1], acc[2 * mt2 + 1][2 * nt2], acc[2 * mt2 + 1][2 * nt2 + 1]),
+              0, 0, 0);
     }
     {
-      // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of tile (mt, nt) in lane l is the pair
-      //   i = I*256 + wm*128 + mt*32 + 8*(r/4) + 4*(l/32) + r%4 ,  j = J*256 + wn*64 + nt*32 + l%32.
+      // acc' = a_ij - s_i/2 - s_j/2 = -dist^2/2 ; register r of block (mt, nt) in lane l is the pair
+      //   i = I*256 + wm*128 + mt*16 + 4*(l/16) + r ,  j = J*256 + wn*64 + nt*16 + l%16.
       const bool diag = a.self && (I == J);
       // a wave tile of a diagonal block that lies entirely below the diagonal holds no pair i <= j
       const bool skip = diag && (wm * 128 >= wn * 64 + 64);
-      // cheap filter: which of the eight 32 x 32 blocks of this wave tile hold a passing pair at all
+      // cheap filter: which of the eight 32 x 32 regions of this wave tile (2 x 2 blocks each, bit mt2*2 + nt2)
+      // hold a passing pair at all
       uint32_t blocks_hit = 0;
       {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
+        for (int mt2 = 0; mt2 < 4; ++mt2) {
 #pragma unroll
-          for (int nt = 0; nt < 2; ++nt) {
-            const float16v& v = acc[mt][nt];
+          for (int nt2 = 0; nt2 < 2; ++nt2) {
+            const float16v& v = R[mt2][nt2];
             float m = fmaxf(fmaxf(v[0], v[1]), v[2]);
 #pragma unroll
             for (int r = 3; r < 15; r += 2) m = fmaxf(fmaxf(m, v[r]), v[r + 1]);
             m = fmaxf(m, v[15]);
-            if (__ballot(m >= a.thr)) blocks_hit |= 1u << (mt * 2 + nt);
+            if (__ballot(m >= a.thr)) blocks_hit |= 1u << (mt2 * 2 + nt2);
           }
         }
-        // the filter of a block only needs that block's last MFMA: let the VALU work of block b run
-        // under the augmentation MFMAs of the blocks after it
+        // the filter of a region only needs that region's MFMA: let the VALU work of a region run
+        // under the augmentation MFMAs of the regions after it
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #pragma unroll
         for (int b = 0; b < 6; ++b) {
@@ -694,24 +823,25 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         while (blocks_hit) {
           const int b = __builtin_ctz(blocks_hit);
           blocks_hit &= blocks_hit - 1;
-          float16v v;
+          float16v v;  // element q = 8 a + 4 c + r : register r of block (2 mt2 + a, 2 nt2 + c)
           switch (b) {
-            case 0: v = acc[0][0]; break;
-            case 1: v = acc[0][1]; break;
-            case 2: v = acc[1][0]; break;
-            case 3: v = acc[1][1]; break;
-            case 4: v = acc[2][0]; break;
-            case 5: v = acc[2][1]; break;
-            case 6: v = acc[3][0]; break;
-            default: v = acc[3][1]; break;
+            case 0: v = R[0][0]; break;
+            case 1: v = R[0][1]; break;
+            case 2: v = R[1][0]; break;
+            case 3: v = R[1][1]; break;
+            case 4: v = R[2][0]; break;
+            case 5: v = R[2][1]; break;
+            case 6: v = R[3][0]; break;
+            default: v = R[3][1]; break;
           }
-          const int mt = b >> 1, nt = b & 1;
+          const int mt2 = b >> 1, nt2 = b & 1;
           const uint32_t nnA = (uint32_t)a.nA, nnB = (uint32_t)a.nB;
-          const uint32_t j = J * TILE + wn * 64 + nt * 32 + r32;
-          const uint32_t ib = I * TILE + wm * 128 + mt * 32 + 4 * hi;
+          const uint32_t jb = J * TILE + wn * 64 + nt2 * 32 + r16;
+          const uint32_t ib = I * TILE + wm * 128 + mt2 * 32 + 4 * g;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const uint32_t i = ib + 8 * (r >> 2) + (r & 3);
+            const uint32_t i = ib + 16 * (r >> 3) + (r & 3);
+            const uint32_t j = jb + 16 * ((r >> 2) & 1);
             // (i, i) belongs to the result by definition, whatever the arithmetic says
             const bool selfp = DIAG && !COUNT && i == j && i < nnA;
             if (__ballot(v[r] >= a.thr || selfp) == 0) continue;  // most registers of a flagged block hold no hit
@@ -749,7 +879,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     }
     // first fragments of the next tile (slice G was certified by the augmentation slice's barrier);
     // read after the filter to keep its registers free
-    load_frags((G % NSTAGE) * STAGE_BYTES, offA[0], offB[0], fa0, fb0);
+    load_first((G % NSTAGE) * STAGE_BYTES);
     I = In;
     J = Jn;
     have = have_next;
@@ -877,12 +1007,12 @@ int ensure_workspace(ejoin_ctx* ctx, int64_t rows, int32_t d) {
   return EJOIN_OK;
 }
 
-int k16_steps(int32_t d) { return (d + KPAD - 1) / KPAD * (KPAD / 16); }
+int k32_steps(int32_t d) { return (d + KPAD - 1) / KPAD * (KPAD / 32); }
 
 int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, uint32_t* max_bits, hipStream_t st) {
-  const int64_t waves = (n + 31) / 32;
+  const int64_t waves = (n + 15) / 16;
   const unsigned blocks = (unsigned)((waves + 3) / 4);
-  hipLaunchKernelGGL(k_norms, dim3(blocks), dim3(256), 0, st, X, n, ld, k16_steps(d), s, max_bits);
+  hipLaunchKernelGGL(k_norms, dim3(blocks), dim3(256), 0, st, X, n, ld, k32_steps(d), s, max_bits);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -1039,7 +1169,7 @@ int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64
     const int64_t chunks = (int64_t)nkb * pad * 4;
     hipLaunchKernelGGL(k_split_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X32, n, pad, d, ld32, nkb, XpA, XpB);
     EJ_TRY(hipGetLastError());
-    const int64_t waves = (n + 31) / 32;
+    const int64_t waves = (n + 15) / 16;
     hipLaunchKernelGGL(k_norms_packed, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, XpA, XpB, n, pad, 3 * nkb, ctx->s,
                        ctx->status + 1);
     EJ_TRY(hipGetLastError());
@@ -1389,7 +1519,7 @@ int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   if ((rc = launch_reset(ctx, nullptr, st)) != EJOIN_OK) return rc;
   if ((rc = launch_norms(ctx, X, n, d, ld, ctx->s, ctx->status + 1, st)) != EJOIN_OK) return rc;
   if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, nullptr, st)) != EJOIN_OK) return rc;
-  hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->H, ctx->status, n, ld, k16_steps(d), i0, j0, rows, cols, out);
+  hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->H, ctx->status, n, ld, k32_steps(d), i0, j0, rows, cols, out);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }

@@ -52,7 +52,7 @@ def test_norms_against_oracle(ej, workload, n):
     s = ej.norms(dev(X)).cpu().numpy().astype(np.float64)
     want = orc.norms(P)
     d = X.shape[1]
-    # one RNE rounding per 16-wide MFMA step on a running sum <= s: |err| <= (d/16 + 1) * 2^-24 * s
+    # one RNE rounding per MFMA step (32-wide; at most d/16 of them) on a running sum <= s: |err| <= (d/16 + 1) * 2^-24 * s
     assert np.all(np.abs(s - want) <= (d / 16 + 1) * 2.0**-24 * want)
 
 
