@@ -554,11 +554,11 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       acc[4 * H + t][NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[t], b, FIRST ? z : acc[4 * H + t][NT], 0, 0, 0);
     }
   };
-  // scheduling hints: `reads` LDS reads, then four MFMAs
-  auto hint = [&](auto reads_c) {
-    constexpr int R = decltype(reads_c)::value;
-    if constexpr (R > 0) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  // scheduling hints: one LDS read, then `M` MFMAs.  The reads of a half step are spread one by one between
+  // its MFMAs (two reads in a row already cost 2-3 %: the MFMA pipe runs dry while the wave issues them).
+  auto read_then_mfma = [&](auto m_c) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, decltype(m_c)::value, 0);
   };
 
   // --- per-wave result staging (pair mode): entries are appended in LDS and written out in bulk
@@ -658,6 +658,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   using I1_ = std::integral_constant<int, 1>;
   using I2_ = std::integral_constant<int, 2>;
   using I3_ = std::integral_constant<int, 3>;
+  using I4_ = std::integral_constant<int, 4>;
+  using I6_ = std::integral_constant<int, 6>;
   // Fragment registers: the A fragments of the two halves of the wave tile and the four B fragments.  A slice
   // starts with faL and fb[0..2] in registers (read under the slice before); fb[3] and faH follow under its first half.
   half8 faL[4], faH[4], fb[4];
@@ -683,10 +685,11 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     mma4(first_c, I0_{}, I1_{}, faL, fb[1]);
     mma4(first_c, I0_{}, I2_{}, faL, fb[2]);
     mma4(first_c, I0_{}, I3_{}, faL, fb[3]);
-    hint(I2_{});
-    hint(I1_{});
-    hint(I1_{});
-    hint(I1_{});
+    read_then_mfma(I3_{});
+    read_then_mfma(I3_{});
+    read_then_mfma(I3_{});
+    read_then_mfma(I3_{});
+    read_then_mfma(I4_{});
     __builtin_amdgcn_sched_barrier(0);  // keep the two halves apart: each has its own interleave pattern
     if constexpr (!LAST) {
       faL[0] = frag(st_nxt, offA, 0);
@@ -700,10 +703,13 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       mma4(first_c, I1_{}, I2_{}, faH, fb[2]);
       fb[2] = frag(st_nxt, offB, 2);
       mma4(first_c, I1_{}, I3_{}, faH, fb[3]);
-      hint(I2_{});
-      hint(I2_{});
-      hint(I2_{});
-      hint(I1_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I4_{});
     } else {
       // the slice that follows is the augmentation slice: its six operands go where the fragments would
       // (faL[t]: A operand of region t, fb[0], fb[1]: B operands)
@@ -718,10 +724,12 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       faL[3] = aug_operand(oa_n, 3);
       mma4(first_c, I1_{}, I2_{}, faH, fb[2]);
       mma4(first_c, I1_{}, I3_{}, faH, fb[3]);
-      hint(I2_{});
-      hint(I2_{});
-      hint(I2_{});
-      hint(I0_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I2_{});
+      read_then_mfma(I6_{});
     }
   };
   // One data slice.  LAST: last data slice of a tile (the fragments read ahead are those of the augmentation
