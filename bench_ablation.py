@@ -73,8 +73,12 @@ def main():
                 ms.append(a + b)
             ej.set_profiling(False)
             found = int(npairs.cpu()[0])
-            if name == "no_symmetry":  # ordered pairs, self pairs included once: 2 * (found_self - n) + n
-                assert found == 2 * (ref_found - n) + n, (found, ref_found)
+            if name == "no_symmetry":
+                # ordered pairs, self pairs included once: 2 * (found_self - n) + n, up to pairs on the threshold itself
+                # (the matrix cores' sum of a step is not symmetric in its operands to the last bit, so (i, j) and
+                # (j, i) of a pair whose distance is epsilon to FP32 resolution can fall on different sides)
+                want = 2 * (ref_found - n) + n
+                assert abs(found - want) <= 1e-6 * want, (found, ref_found)
             elif ref_found is None:
                 ref_found = found
             else:
