@@ -24,7 +24,7 @@
  *   - The squared distance the library works with is, in FP32,
  *         acc' = a_ij - s_i/2 - s_j/2,    d2 = max(0, -2 acc'),    pass  <=>  acc' >= -fl(eps * eps) / 2,
  *     where a_ij and s_i are accumulated over k in ascending order on the matrix cores in steps
- *     of 16 coordinates, and the two norm terms are added by one more matrix-core step (Step 3 of
+ *     of 32 coordinates, and the two norm terms are added by one more matrix-core step (Step 3 of
  *     Section 3.1 folded into the accumulation).  The self pair (i, i) is always reported, with
  *     d2 = 0.  Duplicates of a point are at distance exactly 0 whenever the point's s_i is at least
  *     max(2^-16 s_max, 2^-14), s_max the largest s of the data (the norm term is then carried exactly;
