@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "ejoin.h"
+#include "panel_layout.h"
 #include "tile_cursor.h"
 
 namespace {
@@ -55,38 +56,6 @@ static_assert(NSTAGE == 3 || NSTAGE == 4, "the slice pipeline reads one slice ah
 
 // Device status word written by k_aux, read by the other kernels.
 constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
-
-// LDS layout of a panel: 256 rows of 64 B, four 16-byte chunks each.  Two things decide where the
-// chunk of point r (0..255), coordinates 8 k .. 8 k + 7 (k = 0..3) of the slice, is stored:
-//   * A v_mfma_f32_16x16x32_f16 operand wants, in lane l, point l%16 of a group of 16 and chunk k = l/16.
-//     The LDS serves a ds_read_b128 16 lanes at a time, and which lanes go together is not simply
-//     "16 consecutive": reading rows l%16 at chunk l/16 costs two cycles per group (measured).  A read
-//     in which lane l takes row l%32 of a group of 32 and chunk l/32 is served without conflicts (measured),
-//     so the layout is made such that the MFMA operand IS such a read: points come in groups of 32,
-//     (point 16 h + x, chunk 2 u + v) of a group is stored in row 16 v + x, chunk 2 h + u.  Fragment
-//     t = 2 T + h (points 16 t .. 16 t + 15 of the panel) is then: lane l reads row 32 T + l%32,
-//     chunk 2 h + l/32.
-//   * Chunk c of row r is stored at position c ^ swz(r): 16 consecutive rows at the same chunk
-//     then fall into 16 distinct 16-byte bank groups (the LDS has 64 banks of 4 B; 4 rows per
-//     256 B bank line x 4 positions).  This is the role the XOR swizzle of Section 3.3.5 (Eq. 2)
-//     plays on the A100's 32 banks.
-#ifdef EJOIN_ABL_NOSWIZZLE
-__host__ __device__ __forceinline__ int swz(int) { return 0; }
-#else
-__host__ __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
-#endif
-// Which point (same group of 32) and which chunk of its slice the 16 bytes at (row, position p) hold.
-__host__ __device__ __forceinline__ void stored_at(int64_t row, int p, int64_t& point, int& chunk) {
-  const int c = p ^ swz((int)(row & 255));
-  point = (row & ~(int64_t)31) | ((c >> 1) << 4) | (row & 15);
-  chunk = 2 * (c & 1) + (int)((row >> 4) & 1);
-}
-// The inverse: index of the 16-byte chunk (row * 4 + position) that holds (point, chunk).
-__host__ __device__ __forceinline__ int64_t place_of(int64_t point, int chunk) {
-  const int64_t row = (point & ~(int64_t)31) | ((int64_t)(chunk & 1) << 4) | (point & 15);
-  const int c = 2 * (int)((point >> 4) & 1) + (chunk >> 1);
-  return row * 4 + (c ^ swz((int)(row & 255)));
-}
 
 struct JoinArgs {
   // "points" (rows of the distance matrix) and "query points" (columns); the self-join passes the same set twice
@@ -508,13 +477,10 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // panel layout (see stored_at) that is row l%32 of the fragment's group of 32 rows, chunk 2 h + l/32
   // for fragment t = 2 T + h.  Group T adds 32 rows = 2048 B (swz unchanged: 32 rows = 8 groups of 4).
   uint32_t offA[2], offB[2];
-  {
-    const int rowA = wm * 128 + (lane & 31), rowB = wn * 64 + (lane & 31);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      offA[h] = lds0 + rowA * 64 + (((2 * h + (lane >> 5)) ^ swz(rowA)) << 4);
-      offB[h] = lds0 + PANEL_BYTES + rowB * 64 + (((2 * h + (lane >> 5)) ^ swz(rowB)) << 4);
-    }
+  for (int h = 0; h < 2; ++h) {
+    offA[h] = lds0 + wm * 128 * 64 + fragment_offset(lane, h);
+    offB[h] = lds0 + PANEL_BYTES + wn * 64 * 64 + fragment_offset(lane, h);
   }
   // Operands of the augmentation step (one v_mfma_f32_32x32x16_f16 per 32 x 32 region, see there): lane l
   // supplies row (or column) m = l%32 of the region, k = 8*(l/32) .. +7, and finds its 16 bytes ready made in

@@ -1,0 +1,57 @@
+// Arrangement of an operand panel (256 points x 32 coordinates = 256 rows of 64 bytes) in the LDS, and hence in
+// the packed copy of the data, which the kernel copies to the LDS as it is.  Host- and device-compilable: the CPU
+// tests check it against the operand layout of the MFMA instruction.
+#ifndef EJOIN_PANEL_LAYOUT_H
+#define EJOIN_PANEL_LAYOUT_H
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define EJ_LAYOUT_HD __host__ __device__ __forceinline__
+#else
+#define EJ_LAYOUT_HD inline
+#endif
+
+// A row holds four 16-byte chunks (8 coordinates each).  Two things decide where the chunk of point r
+// (0..255), coordinates 8 k .. 8 k + 7 (k = 0..3) of the slice, is stored:
+//   * A v_mfma_f32_16x16x32_f16 operand wants, in lane l, point l%16 of a group of 16 and chunk k = l/16.
+//     The LDS serves a ds_read_b128 16 lanes at a time, and which lanes go together is not simply
+//     "16 consecutive": reading rows l%16 at chunk l/16 costs two cycles per group (measured).  A read
+//     in which lane l takes row l%32 of a group of 32 and chunk l/32 is served without conflicts (measured),
+//     so the layout is made such that the MFMA operand IS such a read: points come in groups of 32,
+//     (point 16 h + x, chunk 2 u + v) of a group is stored in row 16 v + x, chunk 2 h + u.  Fragment
+//     t = 2 T + h (points 16 t .. 16 t + 15 of the panel) is then: lane l reads row 32 T + l%32,
+//     chunk 2 h + l/32.
+//   * Chunk c of row r is stored at position c ^ swz(r): 16 consecutive rows at the same chunk
+//     then fall into 16 distinct 16-byte bank groups (the LDS has 64 banks of 4 B; 4 rows per
+//     256 B bank line x 4 positions).  This is the role the XOR swizzle of Section 3.3.5 (Eq. 2)
+//     plays on the A100's 32 banks.
+#ifdef EJOIN_ABL_NOSWIZZLE
+EJ_LAYOUT_HD int swz(int) { return 0; }
+#else
+EJ_LAYOUT_HD int swz(int row) { return (row >> 2) & 3; }
+#endif
+
+// Which point (same group of 32) and which chunk of its slice the 16 bytes at (row, position p) hold.
+EJ_LAYOUT_HD void stored_at(int64_t row, int p, int64_t& point, int& chunk) {
+  const int c = p ^ swz((int)(row & 255));
+  point = (row & ~(int64_t)31) | ((int64_t)(c >> 1) << 4) | (row & 15);
+  chunk = 2 * (c & 1) + (int)((row >> 4) & 1);
+}
+
+// The inverse: index of the 16-byte chunk (row * 4 + position) that holds (point, chunk).
+EJ_LAYOUT_HD int64_t place_of(int64_t point, int chunk) {
+  const int64_t row = (point & ~(int64_t)31) | ((int64_t)(chunk & 1) << 4) | (point & 15);
+  const int c = 2 * (int)((point >> 4) & 1) + (chunk >> 1);
+  return row * 4 + (c ^ swz((int)(row & 255)));
+}
+
+// Byte offset inside a panel of the 16 bytes that lane `lane` reads as its part of fragment t (points
+// 16 t .. 16 t + 15 of the panel, as the A or B operand of v_mfma_f32_16x16x32_f16).
+// fragment_offset(lane, t) = fragment_offset(lane, t % 2) + (t / 2) * 2048.
+EJ_LAYOUT_HD uint32_t fragment_offset(int lane, int t) {
+  const int row = 32 * (t >> 1) + (lane & 31), chunk = 2 * (t & 1) + (lane >> 5);
+  return (uint32_t)(row * 64 + ((chunk ^ swz(row)) << 4));
+}
+
+#endif  // EJOIN_PANEL_LAYOUT_H

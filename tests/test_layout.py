@@ -1,0 +1,67 @@
+"""The LDS / packed-copy arrangement of an operand panel (csrc/panel_layout.h compiled with g++): a bijection
+inside every group of 32 points, and such that the 16 bytes lane l reads for fragment t are what the operand
+layout of v_mfma_f32_16x16x32_f16 wants there: point 16 t + l % 16, coordinates 8 (l / 16) .. + 7."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", params=["swizzled", "no_swizzle_ablation"])
+def lay(request, tmp_path_factory):
+    out = tmp_path_factory.mktemp("layout") / f"liblayout_{request.param}.so"
+    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-I", os.path.join(ROOT, "paper_2508_21230_amd", "csrc"),
+           os.path.join(ROOT, "tests", "host", "layout_dump.cpp"), "-o", str(out)]
+    if request.param == "no_swizzle_ablation":
+        cmd.insert(1, "-DEJOIN_ABL_NOSWIZZLE")
+    subprocess.run(cmd, check=True)
+    lib = ctypes.CDLL(str(out))
+    lib.ejoin_test_stored_at.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)]
+    lib.ejoin_test_stored_at.restype = None
+    lib.ejoin_test_place_of.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    lib.ejoin_test_place_of.restype = ctypes.c_int64
+    lib.ejoin_test_fragment_offset.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.ejoin_test_fragment_offset.restype = ctypes.c_uint32
+
+    def stored_at(row, p):
+        point, chunk = ctypes.c_int64(), ctypes.c_int32()
+        lib.ejoin_test_stored_at(row, p, ctypes.byref(point), ctypes.byref(chunk))
+        return point.value, chunk.value
+    lib.stored_at = stored_at
+    lib.kind = request.param
+    return lib
+
+
+def test_every_chunk_of_every_point_has_exactly_one_place(lay):
+    for base in (0, 256, 5 * 256):  # the arrangement repeats per 256-row panel (and per group of 32)
+        seen = set()
+        for row in range(base, base + 256):
+            for p in range(4):
+                point, chunk = lay.stored_at(row, p)
+                assert point // 32 == row // 32 and 0 <= chunk < 4
+                assert lay.ejoin_test_place_of(point, chunk) == row * 4 + p
+                seen.add((point, chunk))
+        assert seen == {(pt, c) for pt in range(base, base + 256) for c in range(4)}
+
+
+def test_a_fragment_read_is_the_mfma_operand(lay):
+    for t in range(16):  # the 16 fragments of a 256-point panel
+        for lane in range(64):
+            off = lay.ejoin_test_fragment_offset(lane, t)
+            assert off % 16 == 0 and off < 256 * 64
+            point, chunk = lay.stored_at(off // 64, (off % 64) // 16)
+            assert (point, chunk) == (16 * t + lane % 16, lane // 16)
+            assert off == lay.ejoin_test_fragment_offset(lane, t % 2) + (t // 2) * 2048
+
+
+def test_sixteen_consecutive_lanes_of_a_read_hit_sixteen_bank_groups(lay):
+    """What the swizzle is for: lanes 16 q .. 16 q + 15 of a fragment read touch every 16-byte bank group once."""
+    if lay.kind != "swizzled":
+        pytest.skip("the ablation build stores rows unpermuted")
+    for t in range(2):
+        for q in range(4):
+            groups = {(lay.ejoin_test_fragment_offset(lane, t) % 256) // 16 for lane in range(16 * q, 16 * q + 16)}
+            assert len(groups) == 16
