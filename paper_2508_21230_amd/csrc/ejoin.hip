@@ -166,12 +166,7 @@ constexpr uint32_t P1_OUT_OF_RANGE = 0xFB53u;  // -60000 in FP16
 // pieces by constants, c (p1 + p2 + p3)_i + c (q1 + q2 + q3)_j = -s_i/2 - s_j/2, every product exact in FP32.
 // H (npad rows) serves the dense-tile kernel.  For the join the operands of the extra step are also
 // written, ready made, as one more k-block behind the packed X (`aug`, may be null), so that the join
-// kernel streams them through the same LDS stages as the data.  Row r of that block, with m = r % 32
-// and b = r - m the first row of its group of 32 (see the augmentation step of k_join for the why):
-//   chunk 0 = { P_x, P_y }, x = b + 16 (m/16) + 8 ((m/4)%2) + m%4, y = x + 4   (A operand, k = 0..7, of row m)
-//   chunk 1 = { P_x, P_y }, x = b + m%16, y = x + 16                            (B operand, k = 8..15, of column m)
-//   chunk 2 = { C, 0 },  chunk 3 = { 0, C }                                     (the indicator halves)
-// chunk c at position c ^ swz(r) like every other block.
+// kernel streams them through the same LDS stages as the data (layout: panel_layout.h, "the augmentation step").
 __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max,
                       uint4* __restrict__ H, uint4* __restrict__ aug) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -206,7 +201,7 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
     const int sw = swz((int)(i & 255));
     const int r = (int)(i & 31);
     const int64_t b = i - r;
-    const int64_t xa = b + 16 * (r >> 4) + 8 * ((r >> 2) & 1) + (r & 3), xb = b + (r & 15);
+    const int64_t xa = b + aug_row_point(r), xb = b + aug_col_point(r);
     const uint2 a0 = pieces(xa), a1 = pieces(xa + 4), b0 = pieces(xb), b1 = pieces(xb + 16);
     uint4* row = aug + i * 4;
     row[0 ^ sw] = make_uint4(a0.x, a0.y, a1.x, a1.y);
@@ -369,26 +364,30 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
     acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[1][1], 0, 0, 0);
   }
   // augmentation operands: H_x = { p1, p2, p3, 0, c, c, c, 0 } (16 bytes): pieces in .x .y, constant in .z .w
-  const int m = lane & 31, upper = lane >> 5;
+  const int m = lane & 31;
   uint4 ha, hb;
   {
-    const int ra = 16 * (m >> 4) + 8 * ((m >> 2) & 1) + (m & 3);
+    const int ra = aug_row_point(m), rb = aug_col_point(m);
     const uint4 h0 = H[row_a(ra)], h1 = H[row_a(ra + 4)];
-    const uint4 q0 = H[row_b(m & 15)], q1 = H[row_b(16 + (m & 15))];
-    const int qc = (m >> 3) & 1, g0 = m >> 4;
-    if (!upper) {
-      ha = make_uint4(h0.x, h0.y, h1.x, h1.y);
-      hb = g0 ? make_uint4(0, 0, q0.z, q0.w) : make_uint4(q0.z, q0.w, 0, 0);
-    } else {
-      ha = qc ? make_uint4(0, 0, h0.z, h0.w) : make_uint4(h0.z, h0.w, 0, 0);
-      hb = make_uint4(q0.x, q0.y, q1.x, q1.y);
+    const uint4 q0 = H[row_b(rb)], q1 = H[row_b(rb + 16)];
+    // the four chunks of the operand rows, as k_aux writes them for the join kernel
+    const uint4 chunks_a[4] = {make_uint4(h0.x, h0.y, h1.x, h1.y), make_uint4(0, 0, 0, 0), make_uint4(h0.z, h0.w, 0, 0), make_uint4(0, 0, h0.z, h0.w)};
+    const uint4 chunks_b[4] = {make_uint4(0, 0, 0, 0), make_uint4(q0.x, q0.y, q1.x, q1.y), make_uint4(q0.z, q0.w, 0, 0), make_uint4(0, 0, q0.z, q0.w)};
+    const int ca = aug_chunk_a(lane), cb = aug_chunk_b(lane);
+    ha = chunks_a[0];
+    hb = chunks_b[1];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (c == ca) ha = chunks_a[c];
+      if (c == cb) hb = chunks_b[c];
     }
   }
   const float16v res = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ha), as_half8(hb), cat4(acc[0][0], acc[0][1], acc[1][0], acc[1][1]), 0, 0, 0);
 #pragma unroll
   for (int q = 0; q < 16; ++q) {
-    const int rr = bi + 16 * (q >> 3) + 4 * g + (q & 3);
-    const int cc = bj + 16 * ((q >> 2) & 1) + r16;
+    int pi, pj;
+    region_pair(lane, q, pi, pj);
+    const int rr = bi + pi, cc = bj + pj;
     if (rr < rows && cc < cols) out[(int64_t)rr * cols + cc] = (i0 + rr == j0 + cc) ? 0.f : fmaxf(-2.f * res[q], 0.f);
   }
 }
@@ -476,11 +475,15 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // lane l supplies point l%16 of the fragment, coordinates 8*(l/16) .. +7 of the 32-wide step; in the
   // panel layout (see stored_at) that is row l%32 of the fragment's group of 32 rows, chunk 2 h + l/32
   // for fragment t = 2 T + h.  Group T adds 32 rows = 2048 B (swz unchanged: 32 rows = 8 groups of 4).
+  // (= fragment_offset(lane, h) of panel_layout.h on top of the wave's first row)
   uint32_t offA[2], offB[2];
+  {
+    const int rowA = wm * 128 + (lane & 31), rowB = wn * 64 + (lane & 31);
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    offA[h] = lds0 + wm * 128 * 64 + fragment_offset(lane, h);
-    offB[h] = lds0 + PANEL_BYTES + wn * 64 * 64 + fragment_offset(lane, h);
+    for (int h = 0; h < 2; ++h) {
+      offA[h] = lds0 + rowA * 64 + (((2 * h + (lane >> 5)) ^ swz(rowA)) << 4);
+      offB[h] = lds0 + PANEL_BYTES + rowB * 64 + (((2 * h + (lane >> 5)) ^ swz(rowB)) << 4);
+    }
   }
   // Operands of the augmentation step (one v_mfma_f32_32x32x16_f16 per 32 x 32 region, see there): lane l
   // supplies row (or column) m = l%32 of the region, k = 8*(l/32) .. +7, and finds its 16 bytes ready made in
@@ -491,8 +494,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   {
     const int m = lane & 31, upper = lane >> 5;
     const int rowA = wm * 128 + m, rowB = wn * 64 + m;
-    const int chunkA = upper ? 2 + ((m >> 3) & 1) : 0;
-    const int chunkB = upper ? 1 : 2 + (m >> 4);
+    const int chunkA = upper ? 2 + ((m >> 3) & 1) : 0;  // aug_chunk_a(lane)
+    const int chunkB = upper ? 1 : 2 + (m >> 4);        // aug_chunk_b(lane)
     offA_aug = lds0 + rowA * 64 + ((chunkA ^ swz(rowA)) << 4);
     offB_aug = lds0 + PANEL_BYTES + rowB * 64 + ((chunkB ^ swz(rowB)) << 4);
   }
@@ -810,6 +813,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
           }
           const int mt2 = b >> 1, nt2 = b & 1;
           const uint32_t nnA = (uint32_t)a.nA, nnB = (uint32_t)a.nB;
+          // region_pair(lane, r) with the lane's part taken out of the loop
           const uint32_t jb = J * TILE + wn * 64 + nt2 * 32 + r16;
           const uint32_t ib = I * TILE + wm * 128 + mt2 * 32 + 4 * g;
 #pragma unroll

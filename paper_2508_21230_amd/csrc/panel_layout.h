@@ -54,4 +54,30 @@ EJ_LAYOUT_HD uint32_t fragment_offset(int lane, int t) {
   return (uint32_t)(row * 64 + ((chunk ^ swz(row)) << 4));
 }
 
+// ---- The augmentation step: one v_mfma_f32_32x32x16_f16 per 32 x 32 region adds -s_i/2 - s_j/2 to the region's
+// accumulators, which are those of four v_mfma_f32_16x16x32_f16 blocks side by side (16 registers).
+// Register q = 8 a + 4 c + r of lane l holds the pair (i, j) of the region (block (a, c), its register r) ...
+EJ_LAYOUT_HD void region_pair(int lane, int q, int& i, int& j) {
+  i = 16 * (q >> 3) + 4 * (lane >> 4) + (q & 3);
+  j = 16 * ((q >> 2) & 1) + (lane & 15);
+}
+// ... and is where the 32 x 32 MFMA puts its element (m, n):
+EJ_LAYOUT_HD void mfma32_element(int lane, int q, int& m, int& n) {
+  m = 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3);
+  n = lane & 31;
+}
+// So the step needs D[m][n] = -s_i/2 - s_j/2 with i = i(m; bit 4 of n), j = j(n % 16; bit 3 of m), which is
+// bilinear in indicator columns.  With P(x) = { p1, p2, p3, 0 } the pieces of -s_x/2 and C = { c, c, c, 0 }:
+//   row m of the A operand = { P(x), P(x + 4), C [bit 3 of m = 0], C [bit 3 of m = 1] },  x = aug_row_point(m)
+//   row n of the B operand = { C [bit 4 of n = 0], C [bit 4 of n = 1], P(y), P(y + 16) },  y = aug_col_point(n)
+// (k = 0..15 left to right).  Of the 16 products of an element 6 are non-zero and each is exact, as in a plain
+// { P, C } . { C, P } step.  The operands are stored ready made in one more 64-byte row per point (point = row,
+// chunk c at position c ^ swz(row)): row m of a group of 32 holds
+//   chunk 0 = { P(x), P(x + 4) }   chunk 1 = { P(y), P(y + 16) }   chunk 2 = { C, 0 }   chunk 3 = { 0, C }
+// and lane l of the MFMA (row or column l % 32, k = 8 (l / 32) .. + 7) reads chunk aug_chunk_a(l) / aug_chunk_b(l).
+EJ_LAYOUT_HD int aug_row_point(int m) { return 16 * (m >> 4) + 8 * ((m >> 2) & 1) + (m & 3); }
+EJ_LAYOUT_HD int aug_col_point(int n) { return n & 15; }
+EJ_LAYOUT_HD int aug_chunk_a(int lane) { return (lane >> 5) ? 2 + ((lane >> 3) & 1) : 0; }
+EJ_LAYOUT_HD int aug_chunk_b(int lane) { return (lane >> 5) ? 1 : 2 + ((lane >> 4) & 1); }
+
 #endif  // EJOIN_PANEL_LAYOUT_H

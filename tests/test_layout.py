@@ -1,6 +1,10 @@
 """The LDS / packed-copy arrangement of an operand panel (csrc/panel_layout.h compiled with g++): a bijection
 inside every group of 32 points, and such that the 16 bytes lane l reads for fragment t are what the operand
-layout of v_mfma_f32_16x16x32_f16 wants there: point 16 t + l % 16, coordinates 8 (l / 16) .. + 7."""
+layout of v_mfma_f32_16x16x32_f16 wants there: point 16 t + l % 16, coordinates 8 (l / 16) .. + 7.
+Also the index algebra of the augmentation step: a 32x32x16 MFMA on the registers of four 16x16 blocks, fed
+with the operands of panel_layout.h, adds to every register the two norm terms of the pair it stands for.
+The operand and result layouts of the two instructions are taken from AMD's CDNA ISA documentation (the GPU
+parity tests are what confirms them on the device)."""
 import ctypes
 import os
 import subprocess
@@ -65,3 +69,45 @@ def test_sixteen_consecutive_lanes_of_a_read_hit_sixteen_bank_groups(lay):
         for q in range(4):
             groups = {(lay.ejoin_test_fragment_offset(lane, t) % 256) // 16 for lane in range(16 * q, 16 * q + 16)}
             assert len(groups) == 16
+
+
+def test_the_augmentation_step_adds_each_register_its_own_pairs_norm_terms(lay):
+    """Integer stand-ins for the pieces: P(x) = (a_x, b_x, c_x, 0), C = (7, 7, 7, 0).  The step must add
+    7 (a + b + c)_i + 7 (a + b + c)_j to the register that holds pair (i, j) of the 32 x 32 region."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    P = np.zeros((32, 4), dtype=np.int64)
+    Q = np.zeros((32, 4), dtype=np.int64)     # the other set's points (two-set join); same layout
+    P[:, :3] = rng.integers(-1000, 1000, size=(32, 3))
+    Q[:, :3] = rng.integers(-1000, 1000, size=(32, 3))
+    C = np.array([7, 7, 7, 0], dtype=np.int64)
+    Z = np.zeros(4, dtype=np.int64)
+
+    def rows(pieces):  # the four chunks of every row of a group's augmentation block, 8 numbers each
+        out = np.zeros((32, 4, 8), dtype=np.int64)
+        for m in range(32):
+            x, y = lay.ejoin_test_aug_row_point(m), lay.ejoin_test_aug_col_point(m)
+            out[m, 0] = np.concatenate([pieces[x], pieces[x + 4]])
+            out[m, 1] = np.concatenate([pieces[y], pieces[y + 16]])
+            out[m, 2] = np.concatenate([C, Z])
+            out[m, 3] = np.concatenate([Z, C])
+        return out
+    blockA, blockB = rows(P), rows(Q)
+    # operands of v_mfma_f32_32x32x16_f16: lane l supplies row (column) l % 32, k = 8 (l / 32) .. + 7
+    A = np.zeros((32, 16), dtype=np.int64)
+    B = np.zeros((32, 16), dtype=np.int64)
+    for lane in range(64):
+        m, k0 = lane % 32, 8 * (lane // 32)
+        A[m, k0:k0 + 8] = blockA[m, lay.ejoin_test_aug_chunk_a(lane)]
+        B[m, k0:k0 + 8] = blockB[m, lay.ejoin_test_aug_chunk_b(lane)]
+    D = A @ B.T
+    assert (np.count_nonzero(A[:, None, :] * B[None, :, :], axis=2) <= 6).all()
+    seen = set()
+    for lane in range(64):
+        for q in range(16):
+            i, j, m, n = (ctypes.c_int32() for _ in range(4))
+            lay.ejoin_test_region_pair(lane, q, ctypes.byref(i), ctypes.byref(j))
+            lay.ejoin_test_mfma32_element(lane, q, ctypes.byref(m), ctypes.byref(n))
+            assert D[m.value, n.value] == 7 * P[i.value].sum() + 7 * Q[j.value].sum()
+            seen.add((i.value, j.value))
+    assert len(seen) == 32 * 32  # every pair of the region in exactly one register
