@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
 constexpr uint32_t P1_OUT_OF_RANGE = 0xFB53u;  // -60000 in FP16
 
 // Augmentation rows.  Step 3 of Section 3.1 (dist^2 = s_i + s_j - 2 a_ij) is folded into the
-// matrix-core accumulation: after the Gram steps one more 16-wide MFMA step adds
+// matrix-core accumulation: after the Gram steps one more MFMA step (16 wide) adds
 // -s_i/2 - s_j/2 to a_ij, so the accumulator ends as acc' = -dist^2 / 2 and the filter becomes a
 // sign-like test against -eps^2/2.  -s/2 is FP32; scaled by 2^-m it is split into three FP16 pieces
 // p1 + p2 + p3, where m puts the largest norm of the data just below 2^16 (s_max / 2 < 2^15 2^m),
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     dirty = true;
   };
 
-  // 32 x 32 blocks of this wave's tile that the diagonal of a diagonal tile crosses (bit mt*2 + nt)
+  // 32 x 32 regions of this wave's tile that the diagonal of a diagonal tile crosses (bit mt2*2 + nt2)
   uint32_t diag_blocks = 0;
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
