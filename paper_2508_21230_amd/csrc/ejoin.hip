@@ -767,16 +767,23 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       // hold a passing pair at all
       uint32_t blocks_hit = 0;
       {
+        // x >= thr for a threshold thr <= 0 reads, on the bit patterns taken as unsigned integers, bits(x) <=
+        // bits(thr) with thr's sign bit set: a positive x has a smaller pattern than any negative number, and a
+        // negative one passes iff its magnitude is at most |thr|.  (A NaN with a clear sign bit would be flagged;
+        // the exact path below compares as floats and drops it.)  Integer minima need no NaN quieting, which
+        // costs the float version two more instructions per region.
+        const uint32_t thr_bits = __float_as_uint(a.thr) | 0x80000000u;
 #pragma unroll
         for (int mt2 = 0; mt2 < 4; ++mt2) {
 #pragma unroll
           for (int nt2 = 0; nt2 < 2; ++nt2) {
             const float16v& v = R[mt2][nt2];
-            float m = fmaxf(fmaxf(v[0], v[1]), v[2]);
+            auto u = [&](int r) { return __float_as_uint(v[r]); };
+            uint32_t m = min(min(u(0), u(1)), u(2));
 #pragma unroll
-            for (int r = 3; r < 15; r += 2) m = fmaxf(fmaxf(m, v[r]), v[r + 1]);
-            m = fmaxf(m, v[15]);
-            if (__ballot(m >= a.thr)) blocks_hit |= 1u << (mt2 * 2 + nt2);
+            for (int r = 3; r < 15; r += 2) m = min(min(m, u(r)), u(r + 1));
+            m = min(m, u(15));
+            if (__ballot(m <= thr_bits)) blocks_hit |= 1u << (mt2 * 2 + nt2);
           }
         }
         // the filter of a region only needs that region's MFMA: let the VALU work of a region run
@@ -784,7 +791,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #pragma unroll
         for (int b = 0; b < 6; ++b) {
-          __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
       }
