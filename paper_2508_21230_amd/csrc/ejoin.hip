@@ -823,8 +823,23 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
           // region_pair(lane, r) with the lane's part taken out of the loop
           const uint32_t jb = J * TILE + wn * 64 + nt2 * 32 + r16;
           const uint32_t ib = I * TILE + wm * 128 + mt2 * 32 + 4 * g;
+          // Which of the region's four 16 x 16 blocks (registers 4 q .. 4 q + 3) hold a candidate at all: the filter's
+          // test again, on a quarter of the registers each.  Usually one does, and the other twelve registers are
+          // not looked at one by one.  (Diagonal tiles scan everything: their self pairs are not found by value.)
+          uint32_t quarters = 0xF;
+          if (!DIAG) {
+            const uint32_t thr_bits = __float_as_uint(a.thr) | 0x80000000u;
+            quarters = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const uint32_t m = min(min(min(__float_as_uint(v[4 * q]), __float_as_uint(v[4 * q + 1])), __float_as_uint(v[4 * q + 2])),
+                                     __float_as_uint(v[4 * q + 3]));
+              if (__ballot(m <= thr_bits)) quarters |= 1u << q;
+            }
+          }
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
+            if (!((quarters >> (r >> 2)) & 1)) continue;
             const uint32_t i = ib + 16 * (r >> 3) + (r & 3);
             const uint32_t j = jb + 16 * ((r >> 2) & 1);
             // (i, i) belongs to the result by definition, whatever the arithmetic says
