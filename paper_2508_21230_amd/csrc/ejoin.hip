@@ -818,6 +818,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
             case 6: v = R[3][0]; break;
             default: v = R[3][1]; break;
           }
+          asm volatile("" : "+v"(v));  // one copy of the region's registers, in one place (the compiler otherwise makes two)
           const int mt2 = b >> 1, nt2 = b & 1;
           const uint32_t nnA = (uint32_t)a.nA, nnB = (uint32_t)a.nB;
           // region_pair(lane, r) with the lane's part taken out of the loop
