@@ -55,7 +55,9 @@ typedef struct ejoin_ctx ejoin_ctx;
 /* Create a context on HIP device `device`.  The context owns a few hundred bytes of device
  * status words and a workspace: 20 bytes per point (the norms s_i and their FP16 split) plus, for
  * the join calls, a re-laid-out copy of X (roundup(n,256) * (roundup(d,64) + 32) * 2 bytes).  The workspace
- * is grown on demand with hipMalloc, or ahead of time by ejoin_reserve.  Host pointer out. */
+ * is grown on demand with hipMalloc, or ahead of time by ejoin_reserve.  A call that has to grow the
+ * workspace frees the old one first, which waits for the device to be idle: only calls that find the
+ * workspace large enough "enqueue and return".  Host pointer out. */
 int ejoin_create(ejoin_ctx** out, int device);
 
 /* Free the context and its device memory.  The caller must have synchronised its streams. */
@@ -161,20 +163,13 @@ int ejoin_set_join_count(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_
 int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, int64_t i0, int64_t j0,
                      int32_t rows, int32_t cols, float* out, void* stream);
 
-/* Blocks until the context's device is idle enough to read the status word of the last join or
- * dense-tile call, and stores it in *status (host pointer):
+/* Waits for the stream of the context's last join or dense-tile call (which must still exist), reads
+ * that call's status word and stores it in *status (host pointer):
  *   0 = ok, 1 = some s_i >= 2^31 (outside the supported data range), 2 = Inf/NaN in the input. */
 #define EJOIN_STATUS_OK 0
 #define EJOIN_STATUS_NORM_RANGE 1
 #define EJOIN_STATUS_NONFINITE 2
 int ejoin_status(ejoin_ctx* ctx, int* status);
-
-/* Kernel timing for benchmarks.  With profiling on, each join call records HIP events around its
- * norm kernel and around its Gram/epilogue kernel on the call's stream.  ejoin_last_kernel_ms
- * waits for those events and returns the two durations in milliseconds (host pointers):
- * norms_ms covers the preparation kernels (reset, norms, FP16 split), join_ms the join kernel. */
-int ejoin_set_profiling(ejoin_ctx* ctx, int on);
-int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* norms_ms, float* join_ms);
 
 /* Number of 256 x 256 output tiles the Gram kernel evaluates for n points (upper triangle,
  * diagonal included): the executed matrix-core work is 2 * 256 * 256 * roundup(d,64) FLOP per tile. */

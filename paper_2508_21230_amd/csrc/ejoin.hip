@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "ejoin.h"
+#include "ejoin_bench.h"
 #include "panel_layout.h"
 #include "tile_cursor.h"
 
@@ -59,12 +60,12 @@ constexpr uint32_t ST_OK = 0, ST_NORM_RANGE = 1, ST_NONFINITE = 2;
 
 struct JoinArgs {
   // "points" (rows of the distance matrix) and "query points" (columns); the self-join passes the same set twice
-  const uint4* XpA;        // packed copy of the points plus their augmentation block, see k_pack / k_aux
+  const uint4* XpA;        // packed copy of the points plus their augmentation block, see k_norms / k_aux
   const uint4* XpB;        // ... of the query points
   int64_t npadA, npadB;    // rows per k-block: the set's size rounded up to a multiple of TILE
   int64_t nA, nB;
   int self;                // 1: self-join (upper triangle, self pairs), 0: two different sets (full rectangle)
-  const uint32_t* status;  // device status word
+  uint32_t* status;        // status block of the workspace (see k_reset)
   int nslices;  // roundup(d, 64) / 32 : k-blocks of data (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntilesA, ntilesB;  // ceil(n / TILE)
@@ -85,14 +86,15 @@ struct JoinArgs {
 // ------------------------------------------------------------------------------------------
 // Small kernels
 // ------------------------------------------------------------------------------------------
-__global__ void k_reset(uint32_t* status_and_max, unsigned long long* c0) {
-  if (status_and_max && threadIdx.x < 8) status_and_max[8 + threadIdx.x] = 0;  // XCD alignment counters
+// Status block of a workspace (64 words): [0] status word, [1] largest norm seen so far in the call (FP32 bits),
+// [8..15] alignment counters of the XCDs.  Between calls [1] and [8..15] are zero: k_aux clears the counters
+// (and the result counter of the call), k_join clears the maximum.  k_reset restores that state after a call
+// that did not get as far as its join kernel, and before every call on the shared static workspace.
+__global__ void k_reset(uint32_t* status_and_max) {
+  if (threadIdx.x < 8) status_and_max[8 + threadIdx.x] = 0;
   if (threadIdx.x == 0) {
-    if (status_and_max) {
-      status_and_max[0] = ST_OK;
-      status_and_max[1] = 0;
-    }
-    if (c0) *c0 = 0;
+    status_and_max[0] = ST_OK;
+    status_and_max[1] = 0;
   }
 }
 
@@ -112,19 +114,36 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 // to a_ij for a duplicate j of i, so duplicates come out at distance exactly 0.  (The paper
 // matches its norm rounding to its tensor cores' for the same reason.)  Also tracks max_i s_i
 // (as FP32 bits; s >= 0 so unsigned order is numeric order, and NaN/Inf sort above every finite value).
-__global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t ld, int k32steps,
-                                               float* __restrict__ s, uint32_t* __restrict__ max_bits) {
+//
+// PACK: the same pass also writes the packed copy of X for the join kernel.  Xp is cut into k-blocks of 32
+// coordinates; block kb holds, for every row r < npad, the 64 bytes of a row of the LDS panel, already
+// arranged the way the LDS wants them (see place_of); points n .. npad-1 are zero.  In this layout a
+// 256-row panel of one k-block is 16 KB of contiguous memory, so the global->LDS copies of the join are
+// straight 1 KB block copies made of full 128-byte lines (in the row-major X a 32-coordinate slice of a
+// row is half a line, and the L2 would be asked for every line twice).  The 16 bytes a lane loads as its
+// part of the MFMA operand (point l%16, chunk l/16 of the k-block) are exactly one chunk of that layout.
+template <bool PACK>
+__global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int k32steps,
+                                               float* __restrict__ s, uint32_t* __restrict__ max_bits, uint4* __restrict__ Xp) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t row0 = blk * 16;
-  if (row0 >= n) return;
-  int64_t row = row0 + (lane & 15);
-  if (row >= n) row = n - 1;
+  if (row0 >= (PACK ? npad : n)) return;
+  const int64_t row_own = row0 + (lane & 15);
+  int64_t at = 0;
+  if (PACK) at = place_of(row_own, lane >> 4);
+  if (PACK && row0 >= n) {  // padding rows only
+    for (int k = 0; k < k32steps; ++k) Xp[(int64_t)k * npad * 4 + at] = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const bool valid = row_own < n;
+  const int64_t row = valid ? row_own : n - 1;
   const half8* p = reinterpret_cast<const half8*>(X + row * ld) + (lane >> 4);
   float4v acc = {0.f, 0.f, 0.f, 0.f};
   for (int k = 0; k < k32steps; ++k) {
     half8 a = p[4 * k];
     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, a, acc, 0, 0, 0);
+    if (PACK) Xp[(int64_t)k * npad * 4 + at] = valid ? __builtin_bit_cast(uint4, a) : make_uint4(0, 0, 0, 0);
   }
   // element (row, col) of the 16 x 16 block sits in lane col + 16 * (row / 4), register row % 4
   const int c = lane & 15, g = lane >> 4;
@@ -167,10 +186,19 @@ constexpr uint32_t P1_OUT_OF_RANGE = 0xFB53u;  // -60000 in FP16
 // H (npad rows) serves the dense-tile kernel.  For the join the operands of the extra step are also
 // written, ready made, as one more k-block behind the packed X (`aug`, may be null), so that the join
 // kernel streams them through the same LDS stages as the data (layout: panel_layout.h, "the augmentation step").
+// The kernel also clears what the join kernel expects to find zero (the join kernel of the call before has
+// finished by now): the XCD alignment counters, the call's result counter `counter` and, in count mode,
+// the per-point counts `counts` (n entries; may be null).
 __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max,
-                      uint4* __restrict__ H, uint4* __restrict__ aug) {
+                      uint4* __restrict__ H, uint4* __restrict__ aug, unsigned long long* __restrict__ counter,
+                      uint32_t* __restrict__ counts) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t mb = status_and_max[1];
+  if (blockIdx.x == 0) {
+    if (threadIdx.x < 8) status_and_max[8 + threadIdx.x] = 0;
+    if (threadIdx.x == 8 && counter) *counter = 0;
+  }
+  if (counts && i < n) counts[i] = 0;
   int m = 0;
   uint32_t st = ST_OK;
   if (mb >= 0x7f800000u) st = ST_NONFINITE;  // Inf or NaN among the norms
@@ -241,35 +269,13 @@ __global__ void k_convert_f32(const float* __restrict__ X32, int64_t n, int32_t 
   *reinterpret_cast<half8*>(X16 + i * ld16 + k0) = h;
 }
 
-// Packed copy of X for the join kernel.  Xp is cut into k-blocks of 32 coordinates; block kb holds,
-// for every row r < npad, the 64 bytes of a row of the LDS panel, already arranged the way the LDS wants
-// them (see stored_at); points n .. npad-1 are zero.  In this layout a 256-row panel of one k-block is
-// 16 KB of contiguous memory, so the global->LDS copies are straight 1 KB block copies made of full
-// 128-byte lines (in the row-major X a 32-coordinate slice of a row is half a line, and the L2 would be
-// asked for every line twice).
-// Thread t writes chunk t of Xp (fully coalesced writes; reads are 16-byte pieces).
-__global__ void k_pack(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int nkb, uint4* __restrict__ Xp) {
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t total = (int64_t)nkb * npad * 4;
-  if (t >= total) return;
-  const int p = (int)(t & 3);
-  const int64_t rk = t >> 2;
-  const int64_t kb = rk / npad, r = rk - kb * npad;
-  int64_t point;
-  int chunk;
-  stored_at(r, p, point, chunk);
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (point < n) v = *reinterpret_cast<const uint4*>(X + point * ld + kb * KSLICE + (chunk << 3));
-  Xp[t] = v;
-}
-
 // Split-FP16 variant (higher accuracy for FP32 inputs).  Each FP32 coordinate is cut into two FP16
 // numbers, x ~ hi + lo with hi = fp16(x), lo = fp16(x - hi) (22 significant bits together), and the
 // inner product is taken as hi.hi + lo.hi + hi.lo (the lo.lo term is below the 22 bits kept).  That is
 // an ordinary inner product of the 3d-dimensional rows A' = [hi | lo | hi] and B' = [hi | hi | lo], so
 // the join kernel runs unchanged on two packed arrays: row operands come from A', column operands from
 // B'.  This kernel writes both arrays straight from the FP32 rows, in the packed k-block layout of
-// k_pack (nkb blocks per part, 3 nkb blocks per array; rows n .. npad-1 and columns d .. are zero).
+// k_norms<true> (nkb blocks per part, 3 nkb blocks per array; rows n .. npad-1 and columns d .. are zero).
 // Thread t handles the 8 coordinates of one 16-byte chunk.
 __global__ void k_split_pack(const float* __restrict__ X32, int64_t n, int64_t npad, int32_t d, int64_t ld32, int nkb,
                              uint4* __restrict__ XpA, uint4* __restrict__ XpB) {
@@ -437,6 +443,8 @@ __device__ __forceinline__ void xcd_align(uint32_t* bar, uint32_t expect) {
 template <bool COUNT>
 __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  // the largest norm of the call has been consumed by k_aux: cleared here for the next call
+  if (blockIdx.x == 0 && threadIdx.x == 0) a.status[1] = 0;
   if (*a.status != ST_OK) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -907,20 +915,34 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   if (COUNT && hits && lane == 0) atomicAdd(a.total, hits);
 }
 
+
+}  // namespace
+
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
+
+namespace {
+
+// Device memory one call works in.
+struct Workspace {
+  uint32_t* status;  // status block, 64 words (see k_reset)
+  float* s;          // norms (4 B per point)
+  uint4* H;          // augmentation rows (16 B per point, padded to a multiple of TILE)
+  uint4* Xp;         // packed copy of X plus the augmentation k-block
+};
+
 }  // namespace
 
 struct ejoin_ctx {
   int device;
   int num_cu;
-  uint32_t* status;  // device: [0] status word, [1] max norm bits
-  float* s;          // workspace: norms (4 B per point)
-  uint4* H;          // workspace: augmentation rows (16 B per point, padded to a multiple of TILE)
-  int64_t s_cap;     // points the two arrays above hold
-  uint4* Xp;         // workspace: packed copy of X
-  int64_t xp_bytes;
+  Workspace ws;      // owned by the context
+  int64_t s_cap;     // points ws.s and ws.H hold
+  int64_t xp_bytes;  // bytes of ws.Xp
+  bool ws_dirty;     // a call on ws did not reach its join kernel: the status block may hold leftovers
+  uint32_t* last_status;          // status block of the last join or dense-tile call, and the stream it ran on
+  hipStream_t last_stream;
   int profiling;
   hipEvent_t ev[4];
   int ev_valid;
@@ -952,52 +974,64 @@ int fail_hip(ejoin_ctx* ctx, hipError_t e, const char* what) {
     hipError_t e_ = (call);                              \
     if (e_ != hipSuccess) return fail_hip(ctx, e_, #call); \
   } while (0)
+#define EJ_RC(call)                 \
+  do {                              \
+    const int rc_ = (call);         \
+    if (rc_ != EJOIN_OK) return rc_; \
+  } while (0)
+
+int64_t pad_rows(int64_t n) { return (n + TILE - 1) / TILE * TILE; }
+int64_t pad_dims(int32_t d) { return ((int64_t)d + KPAD - 1) / KPAD * KPAD; }
+int k_blocks(int32_t d) { return (int)(pad_dims(d) / KSLICE); }  // 32-coordinate k-blocks = MFMA steps per inner product
 
 int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int64_t ld) {
   if (!ctx || !X) return EJOIN_EINVAL;
   if (n < 1 || n >= (int64_t)0xFFFFFFFFll - TILE) return EJOIN_EINVAL;
   if (d < 1 || d > 65536) return EJOIN_EINVAL;
-  const int64_t dk = ((int64_t)d + KPAD - 1) / KPAD * KPAD;
-  if (ld < dk || (ld % KPAD) != 0) return EJOIN_EINVAL;
+  if (ld < pad_dims(d) || (ld % KPAD) != 0) return EJOIN_EINVAL;
   if ((reinterpret_cast<uintptr_t>(X) & 127) != 0) return EJOIN_EINVAL;
   return EJOIN_OK;
 }
 
-int64_t pad_rows(int64_t n) { return (n + TILE - 1) / TILE * TILE; }
-int64_t pad_dims(int32_t d) { return ((int64_t)d + KPAD - 1) / KPAD * KPAD; }
+bool bad_eps(float eps) { return !(eps >= 0.f) || !isfinite(eps); }
 
-// Workspace for `rows` points in total (each set padded to a multiple of TILE).
-// d = 0: only the per-point arrays (norms, augmentation rows); d > 0: also the packed copies.
-int ensure_workspace(ejoin_ctx* ctx, int64_t rows, int32_t d) {
+// Bytes of packed copy for `rows` (padded) points of d coordinates: the data k-blocks plus the augmentation block.
+int64_t packed_bytes(int64_t rows, int64_t dpad) { return rows * (dpad + KSLICE) * 2; }
+
+// The context's own workspace for `rows` points in total (each set padded to a multiple of TILE).
+// dpad = 0: only the per-point arrays (norms, augmentation rows); dpad > 0: also the packed copies.
+// Growing frees the old arrays, which first waits for the device to be idle.
+int ensure_workspace(ejoin_ctx* ctx, int64_t rows, int64_t dpad) {
+  Workspace& w = ctx->ws;
   if (rows > ctx->s_cap) {
-    if (ctx->s || ctx->H) {
+    if (w.s || w.H) {
       EJ_TRY(hipDeviceSynchronize());
-      if (ctx->s) EJ_TRY(hipFree(ctx->s));
-      ctx->s = nullptr;
-      if (ctx->H) EJ_TRY(hipFree(ctx->H));
-      ctx->H = nullptr;
+      if (w.s) EJ_TRY(hipFree(w.s));
+      w.s = nullptr;
+      if (w.H) EJ_TRY(hipFree(w.H));
+      w.H = nullptr;
       ctx->s_cap = 0;
     }
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->s), (size_t)rows * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&ctx->H), (size_t)rows * sizeof(uint4));
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&w.s), (size_t)rows * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&w.H), (size_t)rows * sizeof(uint4));
     if (e != hipSuccess) {
       (void)hipGetLastError();
-      if (ctx->s) (void)hipFree(ctx->s);
-      ctx->s = nullptr;
+      if (w.s) (void)hipFree(w.s);
+      w.s = nullptr;
       if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
       return fail_hip(ctx, e, "hipMalloc(workspace)");
     }
     ctx->s_cap = rows;
   }
-  const int64_t need = d > 0 ? rows * (pad_dims(d) + KSLICE) * 2 : 0;  // data k-blocks + the augmentation block
+  const int64_t need = dpad > 0 ? packed_bytes(rows, dpad) : 0;
   if (need > ctx->xp_bytes) {
-    if (ctx->Xp) {
+    if (w.Xp) {
       EJ_TRY(hipDeviceSynchronize());
-      EJ_TRY(hipFree(ctx->Xp));
-      ctx->Xp = nullptr;
+      EJ_TRY(hipFree(w.Xp));
+      w.Xp = nullptr;
       ctx->xp_bytes = 0;
     }
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->Xp), (size_t)need);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&w.Xp), (size_t)need);
     if (e != hipSuccess) {
       (void)hipGetLastError();
       if (e == hipErrorOutOfMemory) return EJOIN_ENOMEM;
@@ -1008,34 +1042,25 @@ int ensure_workspace(ejoin_ctx* ctx, int64_t rows, int32_t d) {
   return EJOIN_OK;
 }
 
-int k32_steps(int32_t d) { return (d + KPAD - 1) / KPAD * (KPAD / 32); }
-
-int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, uint32_t* max_bits, hipStream_t st) {
-  const int64_t waves = (n + 15) / 16;
-  const unsigned blocks = (unsigned)((waves + 3) / 4);
-  hipLaunchKernelGGL(k_norms, dim3(blocks), dim3(256), 0, st, X, n, ld, k32_steps(d), s, max_bits);
-  EJ_TRY(hipGetLastError());
-  return EJOIN_OK;
-}
-
-int launch_reset(ejoin_ctx* ctx, unsigned long long* counter, hipStream_t st) {
-  hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, ctx->status, counter);
+// Norms of X into s (and, with Xp given, the packed copy of X); max_bits may be null.
+int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, uint32_t* max_bits, uint4* Xp,
+                 hipStream_t st) {
+  const int64_t npad = pad_rows(n);
+  const int64_t waves = ((Xp ? npad : n) + 15) / 16;
+  const dim3 grid((unsigned)((waves + 3) / 4));
+  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp);
+  else hipLaunchKernelGGL(k_norms<false>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
 
 // Augmentation rows of one set from its norms and the running maximum of all norms.
-// aug: where the join wants the set's augmentation k-block (null for the dense-tile call).
-int launch_aux(ejoin_ctx* ctx, const float* s, int64_t n, uint4* H, uint4* aug, hipStream_t st) {
+// aug: where the join wants the set's augmentation k-block (null for the dense-tile call);
+// counter / counts: what the kernel clears on the way (may be null).
+int launch_aux(ejoin_ctx* ctx, uint32_t* status, const float* s, int64_t n, uint4* H, uint4* aug, unsigned long long* counter,
+               uint32_t* counts, hipStream_t st) {
   const int64_t npad = pad_rows(n);
-  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, s, n, npad, ctx->status, H, aug);
-  EJ_TRY(hipGetLastError());
-  return EJOIN_OK;
-}
-
-int launch_pack(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int64_t ld, int nkb, uint4* Xp, hipStream_t st) {
-  const int64_t chunks = (int64_t)nkb * pad_rows(n) * 4;
-  hipLaunchKernelGGL(k_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X, n, pad_rows(n), ld, nkb, Xp);
+  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, s, n, npad, status, H, aug, counter, counts);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -1053,44 +1078,64 @@ struct DeviceGuard {
   }
 };
 
-// XB == nullptr: self-join of XA.
+// Where a call's results go.
+struct Results {
+  uint32_t* pairs = nullptr;
+  float* dist2 = nullptr;
+  uint64_t capacity = 0;
+  uint64_t* n_pairs = nullptr;
+  uint32_t* counts = nullptr;
+  uint32_t* counts_b = nullptr;
+  uint64_t* total = nullptr;
+  unsigned long long* counter(bool count) const { return reinterpret_cast<unsigned long long*>(count ? total : n_pairs); }
+};
+
+// One packed operand set of a join.
+struct Operand {
+  const uint4* Xp;
+  int64_t n, pad;
+};
+
+// Opens a call on workspace w: first profiling event, and the status block brought to its between-calls state
+// if it may not be in it (always for the static scratch, which every context of the device shares).
+int begin_call(ejoin_ctx* ctx, const Workspace& w, bool own, hipStream_t st) {
+  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
+  if (!own || ctx->ws_dirty) {
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, st, w.status);
+    EJ_TRY(hipGetLastError());
+  }
+  if (own) ctx->ws_dirty = true;  // until the join kernel, which leaves the block clean, has been launched
+  ctx->last_status = w.status;
+  ctx->last_stream = st;
+  return EJOIN_OK;
+}
+
+// The join kernel on two packed operand sets whose augmentation blocks are in place.
 template <bool COUNT>
-int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const uint16_t* XB, int64_t nB, int64_t ldB, int32_t d,
-             float eps, uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint32_t* counts_b,
-             uint64_t* total, hipStream_t st) {
-  const bool self = (XB == nullptr);
-  const int64_t padA = pad_rows(nA), padB = self ? 0 : pad_rows(nB);
-  int rc = ensure_workspace(ctx, padA + padB, d);
-  if (rc != EJOIN_OK) return rc;
-  const int nkb = (d + KPAD - 1) / KPAD * (KPAD / KSLICE);
-  float* sA = ctx->s;
-  float* sB = ctx->s + padA;
-  uint4* HA = ctx->H;
-  uint4* HB = ctx->H + padA;
-  uint4* XpA = ctx->Xp;
-  uint4* XpB = ctx->Xp + padA * (int64_t)(nkb + 1) * 4;
+int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, const Operand& B, bool self, int nslices, float eps,
+                const Results& r, hipStream_t st) {
   JoinArgs a;
   memset(&a, 0, sizeof(a));
-  a.XpA = XpA;
-  a.XpB = self ? XpA : XpB;
-  a.npadA = padA;
-  a.npadB = self ? padA : padB;
-  a.nA = nA;
-  a.nB = self ? nA : nB;
+  a.XpA = A.Xp;
+  a.XpB = B.Xp;
+  a.npadA = A.pad;
+  a.npadB = B.pad;
+  a.nA = A.n;
+  a.nB = B.n;
   a.self = self ? 1 : 0;
-  a.status = ctx->status;
-  a.nslices = nkb;
+  a.status = w.status;
+  a.nslices = nslices;
   a.thr = -0.5f * (eps * eps);
-  a.ntilesA = (uint32_t)(padA / TILE);
-  a.ntilesB = (uint32_t)(a.npadB / TILE);
-  a.pairs = pairs;
-  a.dist2 = dist2;
-  a.capacity = capacity;
-  a.n_pairs = reinterpret_cast<unsigned long long*>(n_pairs);
-  a.counts = counts;
-  a.counts_b = counts_b;
-  a.total = reinterpret_cast<unsigned long long*>(total);
-  a.xcd_bar = ctx->status + 8;
+  a.ntilesA = (uint32_t)(A.pad / TILE);
+  a.ntilesB = (uint32_t)(B.pad / TILE);
+  a.pairs = r.pairs;
+  a.dist2 = r.dist2;
+  a.capacity = r.capacity;
+  a.n_pairs = reinterpret_cast<unsigned long long*>(r.n_pairs);
+  a.counts = r.counts;
+  a.counts_b = r.counts_b;
+  a.total = reinterpret_cast<unsigned long long*>(r.total);
+  a.xcd_bar = w.status + 8;
   {
     // re-align the workgroups of each XCD every few hundred microseconds: about 512 slices
     // (measured on MI355X: +12..16 % over never aligning; every tile costs more than it gains)
@@ -1100,30 +1145,13 @@ int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const 
     a.sync_mode = 0;
 #endif
   }
-
-  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
-  if ((rc = launch_reset(ctx, COUNT ? a.total : a.n_pairs, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_norms(ctx, XA, nA, d, ldA, sA, ctx->status + 1, st)) != EJOIN_OK) return rc;
-  if (!self && (rc = launch_norms(ctx, XB, nB, d, ldB, sB, ctx->status + 1, st)) != EJOIN_OK) return rc;
-  // the augmentation rows need the maximum over both sets, so they follow both norm kernels
-  if ((rc = launch_aux(ctx, sA, nA, HA, XpA + (int64_t)nkb * padA * 4, st)) != EJOIN_OK) return rc;
-  if (!self && (rc = launch_aux(ctx, sB, nB, HB, XpB + (int64_t)nkb * padB * 4, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_pack(ctx, XA, nA, ldA, nkb, XpA, st)) != EJOIN_OK) return rc;
-  if (!self && (rc = launch_pack(ctx, XB, nB, ldB, nkb, XpB, st)) != EJOIN_OK) return rc;
-  if (COUNT) {
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nA + 255) / 256)), dim3(256), 0, st, counts, nA, 0u);
-    EJ_TRY(hipGetLastError());
-    if (counts_b) {
-      hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nB + 255) / 256)), dim3(256), 0, st, counts_b, nB, 0u);
-      EJ_TRY(hipGetLastError());
-    }
-  }
   if (ctx->profiling) {
     EJ_TRY(hipEventRecord(ctx->ev[1], st));
     EJ_TRY(hipEventRecord(ctx->ev[2], st));
   }
   hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
   EJ_TRY(hipGetLastError());
+  if (own) ctx->ws_dirty = false;
   if (ctx->profiling) {
     EJ_TRY(hipEventRecord(ctx->ev[3], st));
     ctx->ev_valid = 1;
@@ -1131,140 +1159,112 @@ int run_join(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const 
   return EJOIN_OK;
 }
 
+// Join of FP16 rows in workspace w (the context's own, or a carving of the static scratch).  XB == nullptr: self-join of XA.
+template <bool COUNT>
+int run_join(ejoin_ctx* ctx, const Workspace& w, bool own, const uint16_t* XA, int64_t nA, int64_t ldA, const uint16_t* XB, int64_t nB,
+             int64_t ldB, int32_t d, float eps, const Results& r, hipStream_t st) {
+  const bool self = (XB == nullptr);
+  const int64_t padA = pad_rows(nA), padB = self ? 0 : pad_rows(nB);
+  const int nkb = k_blocks(d);
+  float* sA = w.s;
+  float* sB = w.s + padA;
+  uint4* HA = w.H;
+  uint4* HB = w.H + padA;
+  uint4* XpA = w.Xp;
+  uint4* XpB = w.Xp + padA * (int64_t)(nkb + 1) * 4;
+  EJ_RC(begin_call(ctx, w, own, st));
+  EJ_RC(launch_norms(ctx, XA, nA, d, ldA, sA, w.status + 1, XpA, st));
+  if (!self) EJ_RC(launch_norms(ctx, XB, nB, d, ldB, sB, w.status + 1, XpB, st));
+  // the augmentation rows need the maximum over both sets, so they follow both norm kernels
+  EJ_RC(launch_aux(ctx, w.status, sA, nA, HA, XpA + (int64_t)nkb * padA * 4, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
+  if (!self) EJ_RC(launch_aux(ctx, w.status, sB, nB, HB, XpB + (int64_t)nkb * padB * 4, nullptr, COUNT ? r.counts_b : nullptr, st));
+  const Operand A{XpA, nA, padA}, B{self ? XpA : XpB, self ? nA : nB, self ? padA : padB};
+  return launch_join<COUNT>(ctx, w, own, A, B, self, nkb, eps, r, st);
+}
+
 // Split-FP16 self-join of FP32 rows (see k_split_pack): the same join kernel on 3 * nkb k-blocks.
 template <bool COUNT>
-int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* pairs, float* dist2,
-                   uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint64_t* total, hipStream_t st) {
+int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, const Results& r, hipStream_t st) {
   const int64_t pad = pad_rows(n);
-  const int32_t d3 = 3 * pad_dims(d);
-  int rc = ensure_workspace(ctx, 2 * pad, d3);  // two packed arrays of 3 * nkb data blocks + 1 augmentation block each
-  if (rc != EJOIN_OK) return rc;
-  const int nkb = pad_dims(d) / KSLICE;
-  uint4* XpA = ctx->Xp;
-  uint4* XpB = ctx->Xp + pad * (int64_t)(3 * nkb + 1) * 4;
-  JoinArgs a;
-  memset(&a, 0, sizeof(a));
-  a.XpA = XpA;
-  a.XpB = XpB;
-  a.npadA = a.npadB = pad;
-  a.nA = a.nB = n;
-  a.self = 1;
-  a.status = ctx->status;
-  a.nslices = 3 * nkb;
-  a.thr = -0.5f * (eps * eps);
-  a.ntilesA = a.ntilesB = (uint32_t)(pad / TILE);
-  a.pairs = pairs;
-  a.dist2 = dist2;
-  a.capacity = capacity;
-  a.n_pairs = reinterpret_cast<unsigned long long*>(n_pairs);
-  a.counts = counts;
-  a.total = reinterpret_cast<unsigned long long*>(total);
-  a.xcd_bar = ctx->status + 8;
-  {
-    const int per = 512 / (a.nslices + 1);
-    a.sync_mode = per < 8 ? 8 : (per > 64 ? 64 : per);
-  }
-  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
-  if ((rc = launch_reset(ctx, COUNT ? a.total : a.n_pairs, st)) != EJOIN_OK) return rc;
+  EJ_RC(ensure_workspace(ctx, 2 * pad, 3 * pad_dims(d)));  // two packed arrays of 3 * nkb data blocks + 1 augmentation block each
+  const Workspace& w = ctx->ws;
+  const int nkb = k_blocks(d);
+  uint4* XpA = w.Xp;
+  uint4* XpB = w.Xp + pad * (int64_t)(3 * nkb + 1) * 4;
+  EJ_RC(begin_call(ctx, w, true, st));
   {
     const int64_t chunks = (int64_t)nkb * pad * 4;
     hipLaunchKernelGGL(k_split_pack, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, X32, n, pad, d, ld32, nkb, XpA, XpB);
     EJ_TRY(hipGetLastError());
     const int64_t waves = (n + 15) / 16;
-    hipLaunchKernelGGL(k_norms_packed, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, XpA, XpB, n, pad, 3 * nkb, ctx->s,
-                       ctx->status + 1);
+    hipLaunchKernelGGL(k_norms_packed, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, XpA, XpB, n, pad, 3 * nkb, w.s, w.status + 1);
     EJ_TRY(hipGetLastError());
   }
-  if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, XpA + (int64_t)3 * nkb * pad * 4, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, XpB + (int64_t)3 * nkb * pad * 4, st)) != EJOIN_OK) return rc;
-  if (COUNT) {
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counts, n, 0u);
-    EJ_TRY(hipGetLastError());
-  }
-  if (ctx->profiling) {
-    EJ_TRY(hipEventRecord(ctx->ev[1], st));
-    EJ_TRY(hipEventRecord(ctx->ev[2], st));
-  }
-  hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
-  EJ_TRY(hipGetLastError());
-  if (ctx->profiling) {
-    EJ_TRY(hipEventRecord(ctx->ev[3], st));
-    ctx->ev_valid = 1;
-  }
-  return EJOIN_OK;
+  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, XpA + (int64_t)3 * nkb * pad * 4, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, XpB + (int64_t)3 * nkb * pad * 4, nullptr, nullptr, st));
+  const Operand A{XpA, n, pad}, B{XpB, n, pad};
+  return launch_join<COUNT>(ctx, w, true, A, B, true, 3 * nkb, eps, r, st);
 }
 
 // Two-set join of a prepared point set with query points given as FP16 rows.
 template <bool COUNT>
-int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, int64_t nQ, int64_t ldQ, float eps, uint32_t* pairs,
-                      float* dist2, uint64_t capacity, uint64_t* n_pairs, uint32_t* counts, uint32_t* counts_b, uint64_t* total,
+int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, int64_t nQ, int64_t ldQ, float eps, const Results& r,
                       hipStream_t st) {
   const int32_t d = P->d;
   const int64_t padQ = pad_rows(nQ);
-  int rc = ensure_workspace(ctx, padQ, d);
-  if (rc != EJOIN_OK) return rc;
-  const int nkb = (int)(pad_dims(d) / KSLICE);
-  JoinArgs a;
-  memset(&a, 0, sizeof(a));
-  a.XpA = P->Xp;
-  a.XpB = ctx->Xp;
-  a.npadA = P->pad;
-  a.npadB = padQ;
-  a.nA = P->n;
-  a.nB = nQ;
-  a.self = 0;
-  a.status = ctx->status;
-  a.nslices = nkb;
-  a.thr = -0.5f * (eps * eps);
-  a.ntilesA = (uint32_t)(P->pad / TILE);
-  a.ntilesB = (uint32_t)(padQ / TILE);
-  a.pairs = pairs;
-  a.dist2 = dist2;
-  a.capacity = capacity;
-  a.n_pairs = reinterpret_cast<unsigned long long*>(n_pairs);
-  a.counts = counts;
-  a.counts_b = counts_b;
-  a.total = reinterpret_cast<unsigned long long*>(total);
-  a.xcd_bar = ctx->status + 8;
-  {
-    const int per = 512 / (a.nslices + 1);
-    a.sync_mode = per < 8 ? 8 : (per > 64 ? 64 : per);
-  }
-  if (ctx->profiling) EJ_TRY(hipEventRecord(ctx->ev[0], st));
-  if ((rc = launch_reset(ctx, COUNT ? a.total : a.n_pairs, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_norms(ctx, XQ, nQ, d, ldQ, ctx->s, ctx->status + 1, st)) != EJOIN_OK) return rc;
-  hipLaunchKernelGGL(k_merge_max, dim3(1), dim3(64), 0, st, ctx->status + 1, P->max_bits);
+  EJ_RC(ensure_workspace(ctx, padQ, pad_dims(d)));
+  const Workspace& w = ctx->ws;
+  const int nkb = k_blocks(d);
+  EJ_RC(begin_call(ctx, w, true, st));
+  EJ_RC(launch_norms(ctx, XQ, nQ, d, ldQ, w.s, w.status + 1, w.Xp, st));
+  hipLaunchKernelGGL(k_merge_max, dim3(1), dim3(64), 0, st, w.status + 1, P->max_bits);
   EJ_TRY(hipGetLastError());
   // the augmentation rows of both sets are scaled to the largest norm of the two: those of the prepared set are rewritten
-  if ((rc = launch_aux(ctx, P->s, P->n, P->H, P->Xp + (int64_t)nkb * P->pad * 4, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_aux(ctx, ctx->s, nQ, ctx->H, ctx->Xp + (int64_t)nkb * padQ * 4, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_pack(ctx, XQ, nQ, ldQ, nkb, ctx->Xp, st)) != EJOIN_OK) return rc;
-  if (COUNT) {
-    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((P->n + 255) / 256)), dim3(256), 0, st, counts, P->n, 0u);
-    EJ_TRY(hipGetLastError());
-    if (counts_b) {
-      hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((nQ + 255) / 256)), dim3(256), 0, st, counts_b, nQ, 0u);
-      EJ_TRY(hipGetLastError());
-    }
-  }
-  if (ctx->profiling) {
-    EJ_TRY(hipEventRecord(ctx->ev[1], st));
-    EJ_TRY(hipEventRecord(ctx->ev[2], st));
-  }
-  hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
-  EJ_TRY(hipGetLastError());
-  if (ctx->profiling) {
-    EJ_TRY(hipEventRecord(ctx->ev[3], st));
-    ctx->ev_valid = 1;
-  }
-  return EJOIN_OK;
+  EJ_RC(launch_aux(ctx, w.status, P->s, P->n, P->H, P->Xp + (int64_t)nkb * P->pad * 4, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, nQ, w.H, w.Xp + (int64_t)nkb * padQ * 4, nullptr, COUNT ? r.counts_b : nullptr, st));
+  const Operand A{P->Xp, P->n, P->pad}, B{w.Xp, nQ, padQ};
+  return launch_join<COUNT>(ctx, w, true, A, B, false, nkb, eps, r, st);
 }
 
 int check_f32(const ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32) {
   if (!ctx || !X32) return EJOIN_EINVAL;
   if (n < 1 || n >= (int64_t)0xFFFFFFFFll - TILE || d < 1 || d > 65536 / 4 || ld32 < d) return EJOIN_EINVAL;
-  if ((int64_t)pad_rows(n) * (pad_dims(d) / KSLICE) * 4 / 256 > 0x7FFFFFFFll) return EJOIN_EUNSUPPORTED;
+  if ((int64_t)pad_rows(n) * k_blocks(d) * 4 / 256 > 0x7FFFFFFFll) return EJOIN_EUNSUPPORTED;  // grid of k_split_pack
   return EJOIN_OK;
+}
+
+// Arguments of a pair-list call / a count call that every entry point checks the same way.
+int check_pairs_out(const uint32_t* pairs, uint64_t capacity, const uint64_t* n_pairs, float eps) {
+  return (!n_pairs || (!pairs && capacity > 0) || bad_eps(eps)) ? EJOIN_EINVAL : EJOIN_OK;
+}
+int check_count_out(const uint32_t* counts, const uint64_t* total, float eps) {
+  return (!counts || !total || bad_eps(eps)) ? EJOIN_EINVAL : EJOIN_OK;
+}
+
+Results pair_results(uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs) {
+  Results r;
+  r.pairs = pairs;
+  r.dist2 = dist2;
+  r.capacity = capacity;
+  r.n_pairs = n_pairs;
+  return r;
+}
+Results count_results(uint32_t* counts, uint32_t* counts_b, uint64_t* total) {
+  Results r;
+  r.counts = counts;
+  r.counts_b = counts_b;
+  r.total = total;
+  return r;
+}
+
+// FP16 join on the context's own workspace.
+template <bool COUNT>
+int join_on_ctx(ejoin_ctx* ctx, const uint16_t* XA, int64_t nA, int64_t ldA, const uint16_t* XB, int64_t nB, int64_t ldB, int32_t d,
+                float eps, const Results& r, void* stream) {
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  EJ_RC(ensure_workspace(ctx, pad_rows(nA) + (XB ? pad_rows(nB) : 0), pad_dims(d)));
+  return run_join<COUNT>(ctx, ctx->ws, true, XA, nA, ldA, XB, nB, ldB, d, eps, r, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -1295,8 +1295,8 @@ int ejoin_create(ejoin_ctx** out, int device) {
     delete ctx;
     return EJOIN_EHIP;
   }
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->status), 256);
-  if (e == hipSuccess) e = hipMemset(ctx->status, 0, 256);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->ws.status), 256);
+  if (e == hipSuccess) e = hipMemset(ctx->ws.status, 0, 256);
   for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&ctx->ev[i]);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -1305,6 +1305,7 @@ int ejoin_create(ejoin_ctx** out, int device) {
     ejoin_destroy(ctx);
     return EJOIN_EHIP;
   }
+  ctx->last_status = ctx->ws.status;
   *out = ctx;
   return EJOIN_OK;
 }
@@ -1312,10 +1313,10 @@ int ejoin_create(ejoin_ctx** out, int device) {
 int ejoin_destroy(ejoin_ctx* ctx) {
   if (!ctx) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
-  if (ctx->status) (void)hipFree(ctx->status);
-  if (ctx->s) (void)hipFree(ctx->s);
-  if (ctx->H) (void)hipFree(ctx->H);
-  if (ctx->Xp) (void)hipFree(ctx->Xp);
+  if (ctx->ws.status) (void)hipFree(ctx->ws.status);
+  if (ctx->ws.s) (void)hipFree(ctx->ws.s);
+  if (ctx->ws.H) (void)hipFree(ctx->ws.H);
+  if (ctx->ws.Xp) (void)hipFree(ctx->ws.Xp);
   for (int i = 0; i < 4; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
   delete ctx;
@@ -1326,7 +1327,7 @@ int ejoin_reserve(ejoin_ctx* ctx, int64_t n, int32_t d) {
   if (!ctx || n < 1 || d < 1 || d > 65536) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return ensure_workspace(ctx, pad_rows(n) + TILE, d);  // + TILE: a total split over two sets pads each of them
+  return ensure_workspace(ctx, pad_rows(n) + TILE, pad_dims(d));  // + TILE: a total split over two sets pads each of them
 }
 
 const char* ejoin_strerror(int code) {
@@ -1343,86 +1344,65 @@ const char* ejoin_strerror(int code) {
 const char* ejoin_last_hip_error(const ejoin_ctx* ctx) { return ctx ? ctx->hip_error : ""; }
 
 int ejoin_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float* s, void* stream) {
-  int rc = check_common(ctx, X, n, d, ld);
-  if (rc != EJOIN_OK) return rc;
+  EJ_RC(check_common(ctx, X, n, d, ld));
   if (!s) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return launch_norms(ctx, X, n, d, ld, s, nullptr, static_cast<hipStream_t>(stream));
+  return launch_norms(ctx, X, n, d, ld, s, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* counts,
                          uint64_t* total_pairs, void* stream) {
-  int rc = check_common(ctx, X, n, d, ld);
-  if (rc != EJOIN_OK) return rc;
-  if (!counts || !total_pairs || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
-  DeviceGuard guard(ctx->device);
-  if (!guard.ok) return EJOIN_EHIP;
-  return run_join<true>(ctx, X, n, ld, nullptr, 0, 0, d, eps, nullptr, nullptr, 0, nullptr, counts, nullptr, total_pairs,
-                        static_cast<hipStream_t>(stream));
+  EJ_RC(check_common(ctx, X, n, d, ld));
+  EJ_RC(check_count_out(counts, total_pairs, eps));
+  return join_on_ctx<true>(ctx, X, n, ld, nullptr, 0, 0, d, eps, count_results(counts, nullptr, total_pairs), stream);
 }
 
 int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs,
                          float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
-  int rc = check_common(ctx, X, n, d, ld);
-  if (rc != EJOIN_OK) return rc;
-  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
-  DeviceGuard guard(ctx->device);
-  if (!guard.ok) return EJOIN_EHIP;
-  return run_join<false>(ctx, X, n, ld, nullptr, 0, 0, d, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
-                         static_cast<hipStream_t>(stream));
+  EJ_RC(check_common(ctx, X, n, d, ld));
+  EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
+  return join_on_ctx<false>(ctx, X, n, ld, nullptr, 0, 0, d, eps, pair_results(pairs, dist2, capacity, n_pairs), stream);
 }
 
 int ejoin_selfjoin_count_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* counts,
                              uint64_t* total_pairs, void* stream) {
-  int rc = check_f32(ctx, X32, n, d, ld32);
-  if (rc != EJOIN_OK) return rc;
-  if (!counts || !total_pairs || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  EJ_RC(check_f32(ctx, X32, n, d, ld32));
+  EJ_RC(check_count_out(counts, total_pairs, eps));
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return run_join_split<true>(ctx, X32, n, d, ld32, eps, nullptr, nullptr, 0, nullptr, counts, total_pairs, static_cast<hipStream_t>(stream));
+  return run_join_split<true>(ctx, X32, n, d, ld32, eps, count_results(counts, nullptr, total_pairs), static_cast<hipStream_t>(stream));
 }
 
 int ejoin_selfjoin_pairs_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* pairs,
                              float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
-  int rc = check_f32(ctx, X32, n, d, ld32);
-  if (rc != EJOIN_OK) return rc;
-  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  EJ_RC(check_f32(ctx, X32, n, d, ld32));
+  EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return run_join_split<false>(ctx, X32, n, d, ld32, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr,
-                               static_cast<hipStream_t>(stream));
+  return run_join_split<false>(ctx, X32, n, d, ld32, eps, pair_results(pairs, dist2, capacity, n_pairs), static_cast<hipStream_t>(stream));
 }
 
 int ejoin_join_pairs(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq, int32_t d,
                      float eps, uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
-  int rc = check_common(ctx, P, np, d, ldp);
-  if (rc == EJOIN_OK) rc = check_common(ctx, Q, nq, d, ldq);
-  if (rc != EJOIN_OK) return rc;
-  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
-  DeviceGuard guard(ctx->device);
-  if (!guard.ok) return EJOIN_EHIP;
-  return run_join<false>(ctx, P, np, ldp, Q, nq, ldq, d, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
-                         static_cast<hipStream_t>(stream));
+  EJ_RC(check_common(ctx, P, np, d, ldp));
+  EJ_RC(check_common(ctx, Q, nq, d, ldq));
+  EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
+  return join_on_ctx<false>(ctx, P, np, ldp, Q, nq, ldq, d, eps, pair_results(pairs, dist2, capacity, n_pairs), stream);
 }
 
 int ejoin_join_count(ejoin_ctx* ctx, const uint16_t* P, int64_t np, int64_t ldp, const uint16_t* Q, int64_t nq, int64_t ldq, int32_t d,
                      float eps, uint32_t* counts_p, uint32_t* counts_q, uint64_t* total, void* stream) {
-  int rc = check_common(ctx, P, np, d, ldp);
-  if (rc == EJOIN_OK) rc = check_common(ctx, Q, nq, d, ldq);
-  if (rc != EJOIN_OK) return rc;
-  if (!counts_p || !total || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
-  DeviceGuard guard(ctx->device);
-  if (!guard.ok) return EJOIN_EHIP;
-  return run_join<true>(ctx, P, np, ldp, Q, nq, ldq, d, eps, nullptr, nullptr, 0, nullptr, counts_p, counts_q, total,
-                        static_cast<hipStream_t>(stream));
+  EJ_RC(check_common(ctx, P, np, d, ldp));
+  EJ_RC(check_common(ctx, Q, nq, d, ldq));
+  EJ_RC(check_count_out(counts_p, total, eps));
+  return join_on_ctx<true>(ctx, P, np, ldp, Q, nq, ldq, d, eps, count_results(counts_p, counts_q, total), stream);
 }
 
 int ejoin_set_create(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, void* stream, ejoin_set** out) {
   if (!out) return EJOIN_EINVAL;
   *out = nullptr;
-  int rc = check_common(ctx, X, n, d, ld);
-  if (rc != EJOIN_OK) return rc;
+  EJ_RC(check_common(ctx, X, n, d, ld));
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1432,8 +1412,7 @@ int ejoin_set_create(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   set->n = n;
   set->pad = pad_rows(n);
   set->d = d;
-  const int nkb = (int)(pad_dims(d) / KSLICE);
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&set->Xp), (size_t)set->pad * (size_t)(nkb + 1) * 64);
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&set->Xp), (size_t)packed_bytes(set->pad, pad_dims(d)));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&set->s), (size_t)set->pad * sizeof(float));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&set->H), (size_t)set->pad * sizeof(uint4));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&set->max_bits), 256);
@@ -1443,9 +1422,8 @@ int ejoin_set_create(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
     return e == hipErrorOutOfMemory ? EJOIN_ENOMEM : fail_hip(ctx, e, "hipMalloc(prepared set)");
   }
   hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, set->max_bits, (int64_t)1, 0u);
-  rc = (hipGetLastError() == hipSuccess) ? EJOIN_OK : EJOIN_EHIP;
-  if (rc == EJOIN_OK) rc = launch_norms(ctx, X, n, d, ld, set->s, set->max_bits, st);
-  if (rc == EJOIN_OK) rc = launch_pack(ctx, X, n, ld, nkb, set->Xp, st);
+  int rc = (hipGetLastError() == hipSuccess) ? EJOIN_OK : EJOIN_EHIP;
+  if (rc == EJOIN_OK) rc = launch_norms(ctx, X, n, d, ld, set->s, set->max_bits, set->Xp, st);
   if (rc != EJOIN_OK) {
     (void)hipDeviceSynchronize();
     (void)ejoin_set_destroy(set);
@@ -1469,25 +1447,21 @@ int ejoin_set_destroy(ejoin_set* set) {
 int ejoin_set_join_pairs(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_t nq, int64_t ldq, float eps, uint32_t* pairs,
                          float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
   if (!ctx || !P || P->ctx != ctx) return EJOIN_EINVAL;
-  int rc = check_common(ctx, Q, nq, P->d, ldq);
-  if (rc != EJOIN_OK) return rc;
-  if (!n_pairs || (!pairs && capacity > 0) || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  EJ_RC(check_common(ctx, Q, nq, P->d, ldq));
+  EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return run_join_prepared<false>(ctx, P, Q, nq, ldq, eps, pairs, dist2, capacity, n_pairs, nullptr, nullptr, nullptr,
-                                  static_cast<hipStream_t>(stream));
+  return run_join_prepared<false>(ctx, P, Q, nq, ldq, eps, pair_results(pairs, dist2, capacity, n_pairs), static_cast<hipStream_t>(stream));
 }
 
 int ejoin_set_join_count(ejoin_ctx* ctx, ejoin_set* P, const uint16_t* Q, int64_t nq, int64_t ldq, float eps, uint32_t* counts_p,
                          uint32_t* counts_q, uint64_t* total, void* stream) {
   if (!ctx || !P || P->ctx != ctx) return EJOIN_EINVAL;
-  int rc = check_common(ctx, Q, nq, P->d, ldq);
-  if (rc != EJOIN_OK) return rc;
-  if (!counts_p || !total || !(eps >= 0.f) || !isfinite(eps)) return EJOIN_EINVAL;
+  EJ_RC(check_common(ctx, Q, nq, P->d, ldq));
+  EJ_RC(check_count_out(counts_p, total, eps));
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  return run_join_prepared<true>(ctx, P, Q, nq, ldq, eps, nullptr, nullptr, 0, nullptr, counts_p, counts_q, total,
-                                 static_cast<hipStream_t>(stream));
+  return run_join_prepared<true>(ctx, P, Q, nq, ldq, eps, count_results(counts_p, counts_q, total), static_cast<hipStream_t>(stream));
 }
 
 int ejoin_convert_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, const float* center, float scale,
@@ -1508,19 +1482,18 @@ int ejoin_convert_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, in
 
 int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, int64_t i0, int64_t j0, int32_t rows,
                      int32_t cols, float* out, void* stream) {
-  int rc = check_common(ctx, X, n, d, ld);
-  if (rc != EJOIN_OK) return rc;
+  EJ_RC(check_common(ctx, X, n, d, ld));
   if (!out || rows < 1 || cols < 1 || i0 < 0 || j0 < 0 || i0 + rows > n || j0 + cols > n) return EJOIN_EINVAL;
   if (rows > 32 * 65535 || cols > 32 * 65535) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
-  rc = ensure_workspace(ctx, pad_rows(n), 0);
-  if (rc != EJOIN_OK) return rc;
+  EJ_RC(ensure_workspace(ctx, pad_rows(n), 0));
+  const Workspace& w = ctx->ws;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((rc = launch_reset(ctx, nullptr, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_norms(ctx, X, n, d, ld, ctx->s, ctx->status + 1, st)) != EJOIN_OK) return rc;
-  if ((rc = launch_aux(ctx, ctx->s, n, ctx->H, nullptr, st)) != EJOIN_OK) return rc;
-  hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, ctx->H, ctx->status, n, ld, k32_steps(d), i0, j0, rows, cols, out);
+  EJ_RC(begin_call(ctx, w, true, st));  // (no join kernel follows: the status block stays marked for a reset)
+  EJ_RC(launch_norms(ctx, X, n, d, ld, w.s, w.status + 1, nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, nullptr, nullptr, nullptr, st));
+  hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, w.H, w.status, n, ld, k_blocks(d), i0, j0, rows, cols, out);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -1529,8 +1502,10 @@ int ejoin_status(ejoin_ctx* ctx, int* status) {
   if (!ctx || !status) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
+  // the stream of the last call first: a blocking copy on the null stream does not order against non-blocking streams
+  EJ_TRY(hipStreamSynchronize(ctx->last_stream));
   uint32_t st = 0;
-  EJ_TRY(hipMemcpy(&st, ctx->status, sizeof(st), hipMemcpyDeviceToHost));
+  EJ_TRY(hipMemcpy(&st, ctx->last_status, sizeof(st), hipMemcpyDeviceToHost));
   *status = (int)st;
   return EJOIN_OK;
 }
@@ -1542,7 +1517,7 @@ int ejoin_set_profiling(ejoin_ctx* ctx, int on) {
   return EJOIN_OK;
 }
 
-int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* norms_ms, float* join_ms) {
+int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* prep_ms, float* join_ms) {
   if (!ctx || !ctx->ev_valid) return EJOIN_EINVAL;
   DeviceGuard guard(ctx->device);
   if (!guard.ok) return EJOIN_EHIP;
@@ -1550,7 +1525,7 @@ int ejoin_last_kernel_ms(ejoin_ctx* ctx, float* norms_ms, float* join_ms) {
   float a = 0.f, b = 0.f;
   EJ_TRY(hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
   EJ_TRY(hipEventElapsedTime(&b, ctx->ev[2], ctx->ev[3]));
-  if (norms_ms) *norms_ms = a;
+  if (prep_ms) *prep_ms = a;
   if (join_ms) *join_ms = b;
   return EJOIN_OK;
 }
