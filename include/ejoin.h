@@ -49,6 +49,7 @@ extern "C" {
 #define EJOIN_EUNSUPPORTED (-2) /* device is not gfx950 / shape outside the supported range */
 #define EJOIN_EHIP (-3)         /* a HIP runtime call failed; see ejoin_last_hip_error */
 #define EJOIN_ENOMEM (-4)       /* the context's workspace could not be allocated */
+#define EJOIN_ESCRATCH (-5)     /* ejoin_selfjoin_pairs_noalloc: the problem does not fit the static scratch */
 
 typedef struct ejoin_ctx ejoin_ctx;
 
@@ -106,6 +107,21 @@ int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
  *            (or size it with ejoin_selfjoin_count: needed = total_pairs + n). */
 int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
                          uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
+
+/* For callers that cannot allocate device memory while they run -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: ejoin_selfjoin_pairs with the workspace taken from a
+ * static device array of EJOIN_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU
+ * the library runs on holds it from load to process end) instead of the context's workspace.  The call
+ * allocates and frees nothing, whatever its arguments.  Arguments, results and conventions are those
+ * of ejoin_selfjoin_pairs, and so are the results, bit for bit.  The problem must fit:
+ *     256 + roundup(20 * npad, 512) + npad * (roundup(d,64) + 32) * 2  <=  EJOIN_STATIC_SCRATCH_BYTES,
+ * npad = roundup(n,256) (n = 100,000 at d = 128 does; so does n = 20,000 at d = 960); otherwise
+ * EJOIN_ESCRATCH is returned and nothing is enqueued.  All contexts of a GPU share the one array, which
+ * keeps the last call's contents (the call clears what it needs zero): calls of this entry point that
+ * overlap on one GPU race, also from different contexts or streams. */
+#define EJOIN_STATIC_SCRATCH_BYTES (40u << 20)
+int ejoin_selfjoin_pairs_noalloc(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
+                                 uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
 
 /* Higher-accuracy variant for FP32 data: the self-join of n FP32 rows (device, row stride ld32 >= d
  * elements, no padding or alignment required) with every coordinate carried as two FP16 numbers,

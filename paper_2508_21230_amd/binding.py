@@ -48,6 +48,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.ejoin_selfjoin_count.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
     lib.ejoin_selfjoin_pairs.restype = C.c_int
     lib.ejoin_selfjoin_pairs.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_selfjoin_pairs_noalloc.restype = C.c_int
+    lib.ejoin_selfjoin_pairs_noalloc.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
     lib.ejoin_selfjoin_count_f32.restype = C.c_int
     lib.ejoin_selfjoin_count_f32.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
     lib.ejoin_selfjoin_pairs_f32.restype = C.c_int
@@ -189,6 +191,19 @@ class EJoin:
         self._check(self._lib.ejoin_selfjoin_pairs(self._h, X.data_ptr(), n, d, ld, float(eps), pairs.data_ptr(),
                                                    dist2.data_ptr() if dist2 is not None else None, capacity,
                                                    n_pairs.data_ptr(), self._stream()), self._h)
+        return pairs, dist2, n_pairs
+
+    def selfjoin_pairs_noalloc(self, X: torch.Tensor, eps: float, pairs: torch.Tensor, dist2: torch.Tensor | None,
+                               n_pairs: torch.Tensor, d: int | None = None):
+        """ejoin_selfjoin_pairs_noalloc: the caller supplies every output (pairs int32[capacity, 2], dist2 float32[capacity]
+        or None, n_pairs int64[1]); neither the library nor this method allocates device memory."""
+        n, d, ld = self._x(X, d)
+        capacity = int(pairs.shape[0])
+        if dist2 is not None and dist2.shape[0] < capacity:
+            raise EJoinError("dist2 must hold as many entries as pairs")
+        self._check(self._lib.ejoin_selfjoin_pairs_noalloc(self._h, X.data_ptr(), n, d, ld, float(eps), pairs.data_ptr(),
+                                                           dist2.data_ptr() if dist2 is not None else None, capacity,
+                                                           n_pairs.data_ptr(), self._stream()), self._h)
         return pairs, dist2, n_pairs
 
     @staticmethod

@@ -922,9 +922,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 // Host side
 // ------------------------------------------------------------------------------------------
 
+// Workspace of the allocation-free entry point (ejoin_selfjoin_pairs_noalloc): device memory that exists from
+// the moment the library is loaded, one copy per GPU.  Host code never uses this name as an address; it asks
+// the runtime for the device address once per context (ejoin_create) and passes that to the kernels.
+static __device__ __align__(256) unsigned char scratch[EJOIN_STATIC_SCRATCH_BYTES];
+
 namespace {
 
-// Device memory one call works in.
+// Device memory one call works in: either the context's own (grown on demand) or a carving of the static scratch.
 struct Workspace {
   uint32_t* status;  // status block, 64 words (see k_reset)
   float* s;          // norms (4 B per point)
@@ -941,6 +946,7 @@ struct ejoin_ctx {
   int64_t s_cap;     // points ws.s and ws.H hold
   int64_t xp_bytes;  // bytes of ws.Xp
   bool ws_dirty;     // a call on ws did not reach its join kernel: the status block may hold leftovers
+  unsigned char* static_scratch;  // device address of `scratch` on this context's device
   uint32_t* last_status;          // status block of the last join or dense-tile call, and the stream it ran on
   hipStream_t last_stream;
   int profiling;
@@ -1040,6 +1046,20 @@ int ensure_workspace(ejoin_ctx* ctx, int64_t rows, int64_t dpad) {
     ctx->xp_bytes = need;
   }
   return EJOIN_OK;
+}
+
+// The static scratch cut up for a self-join of `pad` (padded) points of dpad coordinates; false if it does not fit.
+// Every piece starts on a 256-byte boundary.
+bool carve_static(unsigned char* base, int64_t pad, int64_t dpad, Workspace& w) {
+  auto up = [](int64_t x) { return (x + 255) / 256 * 256; };
+  const int64_t off_s = 256, off_H = off_s + up(pad * 4), off_Xp = off_H + up(pad * 16);
+  const int64_t end = off_Xp + packed_bytes(pad, dpad);
+  if (end > (int64_t)EJOIN_STATIC_SCRATCH_BYTES) return false;
+  w.status = reinterpret_cast<uint32_t*>(base);
+  w.s = reinterpret_cast<float*>(base + off_s);
+  w.H = reinterpret_cast<uint4*>(base + off_H);
+  w.Xp = reinterpret_cast<uint4*>(base + off_Xp);
+  return true;
 }
 
 // Norms of X into s (and, with Xp given, the packed copy of X); max_bits may be null.
@@ -1297,6 +1317,8 @@ int ejoin_create(ejoin_ctx** out, int device) {
   }
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->ws.status), 256);
   if (e == hipSuccess) e = hipMemset(ctx->ws.status, 0, 256);
+  // this device's copy of the static scratch (the device is current here)
+  if (e == hipSuccess) e = hipGetSymbolAddress(reinterpret_cast<void**>(&ctx->static_scratch), HIP_SYMBOL(scratch));
   for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&ctx->ev[i]);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -1337,6 +1359,7 @@ const char* ejoin_strerror(int code) {
     case EJOIN_EUNSUPPORTED: return "unsupported device (gfx950 required) or problem size";
     case EJOIN_EHIP: return "HIP runtime error (see ejoin_last_hip_error)";
     case EJOIN_ENOMEM: return "out of device memory for the workspace (20 bytes per point plus a packed copy of X)";
+    case EJOIN_ESCRATCH: return "problem too large for the static scratch of the allocation-free entry point (EJOIN_STATIC_SCRATCH_BYTES)";
     default: return "unknown error code";
   }
 }
@@ -1363,6 +1386,18 @@ int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
   EJ_RC(check_common(ctx, X, n, d, ld));
   EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
   return join_on_ctx<false>(ctx, X, n, ld, nullptr, 0, 0, d, eps, pair_results(pairs, dist2, capacity, n_pairs), stream);
+}
+
+int ejoin_selfjoin_pairs_noalloc(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs,
+                                 float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream) {
+  EJ_RC(check_common(ctx, X, n, d, ld));
+  EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
+  Workspace w;
+  if (!carve_static(ctx->static_scratch, pad_rows(n), pad_dims(d), w)) return EJOIN_ESCRATCH;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  return run_join<false>(ctx, w, false, X, n, ld, nullptr, 0, 0, d, eps, pair_results(pairs, dist2, capacity, n_pairs),
+                         static_cast<hipStream_t>(stream));
 }
 
 int ejoin_selfjoin_count_f32(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64_t ld32, float eps, uint32_t* counts,

@@ -26,7 +26,7 @@ def test_host_only_entry_points():
     import paper_2508_21230_amd as pkg
     lib = pkg.load_library()
     assert lib.ejoin_strerror(0) == b"ok"
-    for code in (-1, -2, -3, -4, -99):
+    for code in (-1, -2, -3, -4, -5, -99):
         assert len(lib.ejoin_strerror(code)) > 0
     # upper-triangular 256 x 256 tiles, diagonal included
     assert pkg.tiles_evaluated(1) == 1 and pkg.tiles_evaluated(256) == 1 and pkg.tiles_evaluated(257) == 3
