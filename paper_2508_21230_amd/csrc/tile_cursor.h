@@ -40,6 +40,7 @@ struct TileCursor {
   uint32_t self, nsbA, nsbB, ntA, ntB;
   uint32_t rem;          // position of this workgroup's next tile, counted from the first tile of the current rectangle
   uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
+  uint32_t fast_left;    // complete super-blocks that follow the current one in its row (see next)
   uint32_t start, stride;  // (row-major ablation only) first tile and stride of this workgroup
   // self_join: upper triangle of an nt x nt grid (nt_a == nt_b); otherwise the whole nt_a x nt_b grid
   EJ_HD void init(uint32_t block, uint32_t nblocks, uint32_t self_join, uint32_t nt_a, uint32_t nt_b) {
@@ -54,6 +55,7 @@ struct TileCursor {
     nsbB = (nt_b + EJ_SB - 1) / EJ_SB;
     rem = block / EJ_NUM_XCD;
     P = Q = sbi = 0;
+    fast_left = 0;
 #ifdef EJOIN_ABL_ROWMAJOR_TILES
     stride = nblocks;
 #endif
@@ -85,6 +87,27 @@ struct TileCursor {
 #endif
     // Everything here is uniform over the workgroup and meant to stay on the scalar unit: 32-bit counters,
     // closed forms for the number of tiles of a rectangle, and real branches around the rare cases.
+    //
+    // The common step first.  All eight wavefronts of a workgroup run this code at the same time, between two
+    // tiles, with nothing else to overlap it: every instruction here is paid eight times on the one scalar unit.
+    // Along a row of super-blocks nearly every rectangle is a complete 8 x 4 one; the last tile came from such
+    // a rectangle (fast_left counts the complete super-blocks that follow it in the row) and the next one is
+    // 32 entries further on, at the same place (rem / 4, rem % 4) of the next rectangle, whose offsets inside
+    // its super-block rotate with the super-block index.
+#ifndef EJOIN_CURSOR_NO_FAST_PATH
+    if (fast_left != 0 && rem - 32u < 32u) {
+      --fast_left;
+      rem -= 32u;
+      ++Q;
+      ++sbi;
+      const uint32_t xp = (xcd + sbi) & 7;
+      I = EJ_UNIFORM(P * EJ_SB + (xp >> 2) * 8 + (rem >> 2));
+      J = EJ_UNIFORM(Q * EJ_SB + (xp & 3) * 4 + (rem & 3));
+      rem += wpx;
+      return true;
+    }
+    fast_left = 0;
+#endif
     while (P < nsbA) {
       const uint32_t xp = (xcd + sbi) & 7;
       const uint32_t a = (xp >> 2) * 8, b = (xp & 3) * 4;  // the rectangle's offsets inside its super-block
@@ -125,6 +148,18 @@ struct TileCursor {
         I = EJ_UNIFORM(I0 + r);
         J = EJ_UNIFORM(J0 + c);
         rem += wpx;
+#ifndef EJOIN_CURSOR_NO_FAST_PATH
+        // Super-blocks (P, Q + 1 ..) that are complete: every column inside the grid (Q' < ntB / 16), every
+        // row too (always so right of the diagonal of the self-join, whose rows end before its columns do),
+        // and off the diagonal (Q' > P; the self-join starts each row on the diagonal, so Q >= P here).
+        // A rectangle of 32 tiles maps position p to (p / 4, p % 4) whatever kind it is, so the fast step
+        // may follow any rectangle; it only requires the ones it enters to be complete.
+        {
+          const uint32_t qf = ntB / EJ_SB;
+          const bool rows_ok = self ? true : (P < ntA / EJ_SB);
+          fast_left = (v == 32u && rows_ok && Q + 1 < qf) ? qf - 1 - Q : 0u;
+        }
+#endif
         return true;
       }
       rem -= v;

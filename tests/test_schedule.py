@@ -11,13 +11,14 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-@pytest.fixture(scope="module", params=["xcd_rectangles", "rowmajor_ablation"])
-def sched(request, tmp_path_factory):
-    out = tmp_path_factory.mktemp("sched") / f"libsched_{request.param}.so"
+def build_schedule(tmp_path_factory, kind):
+    out = tmp_path_factory.mktemp("sched") / f"libsched_{kind}.so"
     cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-I", os.path.join(ROOT, "paper_2508_21230_amd", "csrc"),
            os.path.join(ROOT, "tests", "host", "schedule_dump.cpp"), "-o", str(out)]
-    if request.param == "rowmajor_ablation":
+    if kind == "rowmajor_ablation":
         cmd.insert(1, "-DEJOIN_ABL_ROWMAJOR_TILES")
+    if kind == "no_fast_path":
+        cmd.insert(1, "-DEJOIN_CURSOR_NO_FAST_PATH")
     subprocess.run(cmd, check=True)
     lib = ctypes.CDLL(str(out))
     lib.ejoin_test_schedule.restype = ctypes.c_int64
@@ -28,8 +29,13 @@ def sched(request, tmp_path_factory):
         buf = np.zeros((want + 8, 4), dtype=np.uint32)
         m = lib.ejoin_test_schedule(nblocks, int(self_join), nt_a, nt_b, buf.ctypes.data, want + 8)
         return buf[:min(m, want + 8)], m, want
-    run.kind = request.param
+    run.kind = kind
     return run
+
+
+@pytest.fixture(scope="module", params=["xcd_rectangles", "rowmajor_ablation"])
+def sched(request, tmp_path_factory):
+    return build_schedule(tmp_path_factory, request.param)
 
 
 CASES = [(256, True, t, t) for t in (1, 2, 3, 15, 16, 17, 31, 32, 33, 40, 100, 391)] + \
@@ -72,3 +78,19 @@ def test_workgroups_of_an_xcd_stay_together(sched, nblocks, self_join, nt_a, nt_
             # next; partially empty rectangles (diagonal, ragged edge) hold fewer tiles, so more of them fit
             if all(full(r) for r in rect):
                 assert len(rect) <= 2, f"XCD {x} step {s}: workgroups spread over {len(rect)} full rectangles"
+
+
+@pytest.mark.parametrize("nblocks,self_join,nt_a,nt_b", CASES + [(256, True, 1000, 1000), (256, False, 700, 333), (256, True, 784, 784),
+                                                                 (248, True, 500, 500), (256, False, 48, 1600)])
+def test_fast_step_gives_the_same_sequence_as_the_general_step(tmp_path_factory, nblocks, self_join, nt_a, nt_b):
+    """The cursor's shortcut for runs of complete rectangles is an optimisation only: workgroup by workgroup, step by
+    step, it yields the tiles the general enumeration yields."""
+    global _pair
+    try:
+        fast, slow = _pair
+    except NameError:
+        _pair = fast, slow = build_schedule(tmp_path_factory, "xcd_rectangles"), build_schedule(tmp_path_factory, "no_fast_path")
+    a, ma, want = fast(nblocks, self_join, nt_a, nt_b)
+    b, mb, _ = slow(nblocks, self_join, nt_a, nt_b)
+    assert ma == mb == want
+    assert np.array_equal(a, b)
