@@ -9,6 +9,14 @@ symmetry" runs the full library's two-set join of the data with itself (every ti
 Prints one JSON line per (variant, workload) and a markdown table.
 
     python bench_ablation.py [--workloads 3,4,5] [--steps 2]
+    python bench_ablation.py --variant no_swizzle --workloads 3 --n 400000 --steps 1     (one variant: counter runs under rocprofv3)
+    python bench_ablation.py --experiments [--workloads 3,4,5]
+
+--experiments runs the two timing-only builds (results meaningless, see the top of csrc/ejoin.hip):
+  hot_panels   every copy hits in the L2; join time and shader clock beside the full kernel's on the same data --
+               what the memory-side fetch of the operand panels costs in clock on real operands;
+  cycle_marks  s_memtime marks between the sections of a tile -- where a tile's time goes, per kind of wavefront.
+Each variant also passes the parity rule against the CPU oracle on small cases (tests/test_gpu_ablations.py).
 """
 from __future__ import annotations
 
@@ -27,7 +35,11 @@ def main():
     ap.add_argument("--workloads", default="3,4,5")
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--n", type=int, default=None, help="override the number of points (quick runs)")
+    ap.add_argument("--variant", default=None, help="run this variant only ('full', 'no_symmetry' or a name of build.ABLATIONS)")
+    ap.add_argument("--experiments", action="store_true", help="run the timing-only builds hot_panels and cycle_marks instead")
     args = ap.parse_args()
+    if args.experiments:
+        return experiments(args)
 
     import numpy as np
     import torch
@@ -45,6 +57,10 @@ def main():
             sys.exit(f"{path} is missing: run `python -m paper_2508_21230_amd.build --ablations` first")
         variants.append((name, path))
     variants.append(("no_symmetry", None))
+    if args.variant:
+        variants = [v for v in variants if v[0] == args.variant]
+        if not variants:
+            sys.exit(f"unknown variant {args.variant}")
     table = {}
     workloads = [int(w) for w in args.workloads.split(",")]
     for w in workloads:
@@ -77,8 +93,9 @@ def main():
                 # ordered pairs, self pairs included once: 2 * (found_self - n) + n, up to pairs on the threshold itself
                 # (the matrix cores' sum of a step is not symmetric in its operands to the last bit, so (i, j) and
                 # (j, i) of a pair whose distance is epsilon to FP32 resolution can fall on different sides)
-                want = 2 * (ref_found - n) + n
-                assert abs(found - want) <= 1e-6 * want, (found, ref_found)
+                if ref_found is not None:
+                    want = 2 * (ref_found - n) + n
+                    assert abs(found - want) <= 1e-6 * want, (found, ref_found)
             elif ref_found is None:
                 ref_found = found
             else:
@@ -90,6 +107,8 @@ def main():
             print(json.dumps(rec), flush=True)
             ej.close()
         del pairs, d2, Xd
+    if args.variant:
+        return
     print("\n| variant | " + " | ".join(f"w{w}: ms | TFLOP/s (2n²d/t) | vs full" for w in workloads) + " |")
     print("|---|" + "---|---|---|" * len(workloads))
     for name, _ in variants:
@@ -98,6 +117,76 @@ def main():
             r, f = table[(name, w)], table[("full", w)]
             cells.append(f"{r['ms']:.1f} | {r['derived_tflops']:.0f} | {r['derived_tflops'] / f['derived_tflops']:.2f}")
         print(f"| {name} | " + " | ".join(cells) + " |")
+
+
+def sclk_mhz():
+    import glob
+    import re
+    for p in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        m = re.search(r"(\d+)\s*Mhz\s*\*", open(p).read())
+        if m:
+            return int(m.group(1))
+    return 0
+
+
+def experiments(args):
+    import time
+
+    import numpy as np
+    import torch
+
+    import datagen
+    import paper_2508_21230_amd as pkg
+    from paper_2508_21230_amd import build
+
+    with open(os.path.join(ROOT, "paper_2508_21230_amd", "workloads_eps.json")) as f:
+        eps_all = json.load(f)
+    sections = ["tile switch (cursor, first fragments)", "first data slice", "middle data slices", "last data slice",
+                "augmentation slice: wait + barrier", "augmentation slice: copy issue", "augmentation MFMAs + filter + exact path"]
+    for w in [int(x) for x in args.workloads.split(",")]:
+        spec = datagen.WORKLOADS[w]
+        n, d, S = args.n or spec["n"], spec["d"], spec["selectivity"][0]
+        eps = float(eps_all[str(w)]["eps"][str(S)]["eps"])
+        Xd = torch.from_numpy(datagen.generate(w, n=n).view(np.int16)).to("cuda:0")
+        cap = int(n * (S / 2 + 1) * 1.6 * (n / spec["n"])) + (1 << 20)
+        pairs = torch.empty((cap, 2), dtype=torch.int32, device="cuda:0")
+        d2 = torch.empty(cap, dtype=torch.float32, device="cuda:0")
+        npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        tiles = pkg.tiles_evaluated(n)
+        flop = 2.0 * 65536 * ((d + 63) // 64 * 64) * tiles
+        for name in ("full", "hot_panels", "full", "hot_panels"):
+            ej = pkg.EJoin(0, lib_path=None if name == "full" else os.path.join(build.ABLATION_DIR, f"libejoin_{name}.so"))
+            step = lambda: ej.selfjoin_pairs(Xd, eps, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
+            step()
+            torch.cuda.synchronize()
+            ej.set_profiling(True)
+            ms, clk = [], []
+            for _ in range(args.steps):
+                step()
+                time.sleep(0.4 * 1e-3 * max(ms[-1] if ms else 100.0, 10.0))  # sample the clock while the kernel runs
+                clk.append(sclk_mhz())
+                ms.append(ej.last_kernel_ms()[1])
+            ej.set_profiling(False)
+            t = sum(ms) / len(ms)
+            print(json.dumps({"experiment": name, "workload": w, "n": n, "d": d, "join_ms": t, "executed_tflops": flop / t / 1e9,
+                              "frac_of_peak": flop / t / 1e9 / 2500.0, "sclk_MHz": sum(clk) / len(clk)}), flush=True)
+            ej.close()
+        ej = pkg.EJoin(0, lib_path=os.path.join(build.ABLATION_DIR, "libejoin_cycle_marks.so"))
+        ej.selfjoin_pairs(Xd, eps, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
+        torch.cuda.synchronize()
+        marks = pairs.view(torch.int64).flatten()[cap - 16:cap]
+        marks.zero_()
+        ej.set_profiling(True)
+        ej.selfjoin_pairs(Xd, eps, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
+        ms = ej.last_kernel_ms()[1]
+        torch.cuda.synchronize()
+        v = marks.cpu().numpy().astype(float) / (4.0 * tiles)  # 4 wavefronts of each kind per workgroup, tiles / 256 tiles per workgroup, 256 workgroups
+        rec = {"experiment": "cycle_marks", "workload": w, "n": n, "d": d, "join_ms": ms, "unit": "s_memtime ticks per tile and wavefront",
+               "waves_0_3_no_copies": {sections[k]: round(v[k], 1) for k in range(7)}, "waves_4_7_copying": {sections[k]: round(v[8 + k], 1) for k in range(7)},
+               "ticks_per_tile": round(v[:8].sum(), 1), "mfma_ticks_if_busy": "1024 cycles per data slice and SIMD, 512 for the augmentation step"}
+        print(json.dumps(rec), flush=True)
+        ej.close()
+        del pairs, d2, Xd
 
 
 if __name__ == "__main__":

@@ -27,6 +27,11 @@ ABLATIONS = {
     "no_xcd_align": ["-DEJOIN_ABL_NOALIGN"],
     "no_prefilter": ["-DEJOIN_ABL_NOPREFILTER"],
 }
+#: measurement builds whose results are meaningless (timing only; see the top of csrc/ejoin.hip and bench_ablation.py --experiments)
+EXPERIMENTS = {
+    "hot_panels": ["-DEJOIN_EXP_HOT_PANELS"],
+    "cycle_marks": ["-DEJOIN_EXP_CYCLE_MARKS"],
+}
 ABLATION_DIR = os.path.join(PKG, "ablation")
 
 
@@ -51,9 +56,11 @@ def build_library(verbose: bool = False) -> str:
 
 
 def build_ablations(verbose: bool = False) -> dict:
-    """Compile the ablation variants -> ablation/libejoin_<name>.so (measurement only, see bench_ablation.py)."""
+    """Compile the ablation variants and the two timing-only experiment builds -> ablation/libejoin_<name>.so
+    (measurement only, see bench_ablation.py)."""
     os.makedirs(ABLATION_DIR, exist_ok=True)
-    return {name: _compile(os.path.join(ABLATION_DIR, f"libejoin_{name}.so"), defs, verbose) for name, defs in ABLATIONS.items()}
+    return {name: _compile(os.path.join(ABLATION_DIR, f"libejoin_{name}.so"), defs, verbose)
+            for name, defs in {**ABLATIONS, **EXPERIMENTS}.items()}
 
 
 if __name__ == "__main__":

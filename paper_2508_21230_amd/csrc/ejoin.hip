@@ -40,6 +40,18 @@ constexpr int KSLICE = 32;    // coordinates per LDS stage (64 B per row)
 #ifndef EJOIN_ABL_NSTAGE
 #define EJOIN_ABL_NSTAGE 4
 #endif
+// Two measurement builds whose RESULTS ARE MEANINGLESS (timing only, never loaded by the product path or the tests):
+// EJOIN_EXP_HOT_PANELS: every global->LDS copy reads one of four panels, so that every copy hits in the L2 while
+//   tiles, MFMAs, LDS traffic and operand values stay what they are -- what the memory-side fetch costs in clock.
+// EJOIN_EXP_CYCLE_MARKS: s_memtime marks between the sections of a tile; the per-section sums of all wavefronts
+//   are added into the last 16 u64 of the pair buffer (waves 0-3, then waves 4-7) -- where a tile's cycles go.
+#ifdef EJOIN_EXP_HOT_PANELS
+#define EJ_PANEL_A(I) ((I) & 1u)
+#define EJ_PANEL_B(J) (2u + ((J) & 1u))
+#else
+#define EJ_PANEL_A(I) (I)
+#define EJ_PANEL_B(J) (J)
+#endif
 constexpr int NSTAGE = EJOIN_ABL_NSTAGE;  // ring of LDS stages; NSTAGE-1 slices are in flight from L2/HBM
 constexpr int DIST = NSTAGE - 1;
 constexpr int THREADS = 512;  // 8 wavefronts: 2 (rows) x 4 (columns), wave tile 128 x 64
@@ -62,7 +74,6 @@ struct JoinArgs {
   // "points" (rows of the distance matrix) and "query points" (columns); the self-join passes the same set twice
   const uint4* XpA;        // packed copy of the points plus their augmentation block, see k_norms / k_aux
   const uint4* XpB;        // ... of the query points
-  int64_t npadA, npadB;    // rows per k-block: the set's size rounded up to a multiple of TILE
   int64_t nA, nB;
   int self;                // 1: self-join (upper triangle, self pairs), 0: two different sets (full rectangle)
   uint32_t* status;        // status block of the workspace (see k_reset)
@@ -115,16 +126,17 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 // matches its norm rounding to its tensor cores' for the same reason.)  Also tracks max_i s_i
 // (as FP32 bits; s >= 0 so unsigned order is numeric order, and NaN/Inf sort above every finite value).
 //
-// PACK: the same pass also writes the packed copy of X for the join kernel.  Xp is cut into k-blocks of 32
-// coordinates; block kb holds, for every row r < npad, the 64 bytes of a row of the LDS panel, already
-// arranged the way the LDS wants them (see place_of); points n .. npad-1 are zero.  In this layout a
-// 256-row panel of one k-block is 16 KB of contiguous memory, so the global->LDS copies of the join are
-// straight 1 KB block copies made of full 128-byte lines (in the row-major X a 32-coordinate slice of a
-// row is half a line, and the L2 would be asked for every line twice).  The 16 bytes a lane loads as its
-// part of the MFMA operand (point l%16, chunk l/16 of the k-block) are exactly one chunk of that layout.
+// PACK: the same pass also writes the packed copy of X for the join kernel.  A panel (256 points) is cut into
+// k-blocks of 32 coordinates; a k-block holds, for each of the panel's rows, the 64 bytes of a row of the LDS
+// panel, already arranged the way the LDS wants them (see place_of); points n .. npad-1 are zero.  A k-block is
+// 16 KB of contiguous memory, so the global->LDS copies of the join are straight 1 KB block copies made of full
+// 128-byte lines (in the row-major X a 32-coordinate slice of a row is half a line, and the L2 would be asked for
+// every line twice), and the `blocks` k-blocks of a panel follow each other (packed_index).  The 16 bytes a lane
+// loads as its part of the MFMA operand (point l%16, chunk l/16 of the k-block) are exactly one chunk of that layout.
 template <bool PACK>
 __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int k32steps,
-                                               float* __restrict__ s, uint32_t* __restrict__ max_bits, uint4* __restrict__ Xp) {
+                                               float* __restrict__ s, uint32_t* __restrict__ max_bits, uint4* __restrict__ Xp,
+                                               int blocks /* k-blocks per panel of Xp: k32steps + 1 */) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t row0 = blk * 16;
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   int64_t at = 0;
   if (PACK) at = place_of(row_own, lane >> 4);
   if (PACK && row0 >= n) {  // padding rows only
-    for (int k = 0; k < k32steps; ++k) Xp[(int64_t)k * npad * 4 + at] = make_uint4(0, 0, 0, 0);
+    for (int k = 0; k < k32steps; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
     return;
   }
   const bool valid = row_own < n;
@@ -143,7 +155,7 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   for (int k = 0; k < k32steps; ++k) {
     half8 a = p[4 * k];
     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, a, acc, 0, 0, 0);
-    if (PACK) Xp[(int64_t)k * npad * 4 + at] = valid ? __builtin_bit_cast(uint4, a) : make_uint4(0, 0, 0, 0);
+    if (PACK) Xp[packed_index(at, k, blocks)] = valid ? __builtin_bit_cast(uint4, a) : make_uint4(0, 0, 0, 0);
   }
   // element (row, col) of the 16 x 16 block sits in lane col + 16 * (row / 4), register row % 4
   const int c = lane & 15, g = lane >> 4;
@@ -184,14 +196,15 @@ constexpr uint32_t P1_OUT_OF_RANGE = 0xFB53u;  // -60000 in FP16
 // 16-byte row is  H_i = { P_i, C } = { p1, p2, p3, 0, c, c, c, 0 }; the extra step multiplies
 // pieces by constants, c (p1 + p2 + p3)_i + c (q1 + q2 + q3)_j = -s_i/2 - s_j/2, every product exact in FP32.
 // H (npad rows) serves the dense-tile kernel.  For the join the operands of the extra step are also
-// written, ready made, as one more k-block behind the packed X (`aug`, may be null), so that the join
-// kernel streams them through the same LDS stages as the data (layout: panel_layout.h, "the augmentation step").
+// written, ready made, as one more k-block behind the data k-blocks of each panel of the packed set (`Xp`,
+// may be null; k-block `aug_kb` of `blocks`), so that the join kernel streams them through the same LDS
+// stages as the data (layout: panel_layout.h, "the augmentation step").
 // The kernel also clears what the join kernel expects to find zero (the join kernel of the call before has
 // finished by now): the XCD alignment counters, the call's result counter `counter` and, in count mode,
 // the per-point counts `counts` (n entries; may be null).
 __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint32_t* __restrict__ status_and_max,
-                      uint4* __restrict__ H, uint4* __restrict__ aug, unsigned long long* __restrict__ counter,
-                      uint32_t* __restrict__ counts) {
+                      uint4* __restrict__ H, uint4* __restrict__ Xp, int aug_kb, int blocks,
+                      unsigned long long* __restrict__ counter, uint32_t* __restrict__ counts) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t mb = status_and_max[1];
   if (blockIdx.x == 0) {
@@ -225,13 +238,13 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
   const uint2 cc = (i >= n || st == ST_OK) ? make_uint2(bits(c) | (bits(c) << 16), bits(c)) : make_uint2(0u, 0u);
   const uint2 own = pieces(i);
   H[i] = make_uint4(own.x, own.y, cc.x, cc.y);
-  if (aug) {
+  if (Xp) {
     const int sw = swz((int)(i & 255));
     const int r = (int)(i & 31);
     const int64_t b = i - r;
     const int64_t xa = b + aug_row_point(r), xb = b + aug_col_point(r);
     const uint2 a0 = pieces(xa), a1 = pieces(xa + 4), b0 = pieces(xb), b1 = pieces(xb + 16);
-    uint4* row = aug + i * 4;
+    uint4* row = Xp + packed_index(i * 4, aug_kb, blocks);
     row[0 ^ sw] = make_uint4(a0.x, a0.y, a1.x, a1.y);
     row[1 ^ sw] = make_uint4(b0.x, b0.y, b1.x, b1.y);
     row[2 ^ sw] = make_uint4(cc.x, cc.y, 0u, 0u);
@@ -279,6 +292,7 @@ __global__ void k_convert_f32(const float* __restrict__ X32, int64_t n, int32_t 
 // Thread t handles the 8 coordinates of one 16-byte chunk.
 __global__ void k_split_pack(const float* __restrict__ X32, int64_t n, int64_t npad, int32_t d, int64_t ld32, int nkb,
                              uint4* __restrict__ XpA, uint4* __restrict__ XpB) {
+  const int blocks = 3 * nkb + 1;  // k-blocks per panel of either array
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = (int64_t)nkb * npad * 4;
   if (t >= total) return;
@@ -300,13 +314,15 @@ __global__ void k_split_pack(const float* __restrict__ X32, int64_t n, int64_t n
     lo[k] = (_Float16)rest;
   }
   const uint4 vh = __builtin_bit_cast(uint4, hi), vl = __builtin_bit_cast(uint4, lo);
-  const int64_t part = (int64_t)nkb * npad * 4;
-  XpA[t] = vh;
-  XpA[t + part] = vl;
-  XpA[t + 2 * part] = vh;
-  XpB[t] = vh;
-  XpB[t + part] = vh;
-  XpB[t + 2 * part] = vl;
+  const int64_t place = r * 4 + p;
+  const int64_t i0 = packed_index(place, (int)kb, blocks), i1 = packed_index(place, nkb + (int)kb, blocks),
+                i2 = packed_index(place, 2 * nkb + (int)kb, blocks);
+  XpA[i0] = vh;
+  XpA[i1] = vl;
+  XpA[i2] = vh;
+  XpB[i0] = vh;
+  XpB[i1] = vh;
+  XpB[i2] = vl;
 }
 
 // Norms for the split variant: s_i = A'_i . B'_i, accumulated by the same MFMA steps in the same
@@ -323,7 +339,7 @@ __global__ __launch_bounds__(256) void k_norms_packed(const uint4* __restrict__ 
   const int64_t at = place_of(row0 + (lane & 15), g);  // (< npad: points past n are zero)
   float4v acc = {0.f, 0.f, 0.f, 0.f};
   for (int kb = 0; kb < nkb_total; ++kb) {
-    const int64_t off = (int64_t)kb * npad * 4 + at;
+    const int64_t off = packed_index(at, kb, nkb_total + 1);
     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(XpA[off]), as_half8(XpB[off]), acc, 0, 0, 0);
   }
   const int c = lane & 15;
@@ -463,7 +479,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // SIMDs with 4..7 one to one, issue none and keep the MFMA pipes busy meanwhile.
   const char* XbA = reinterpret_cast<const char*>(a.XpA);
   const char* XbB = reinterpret_cast<const char*>(a.XpB);
-  const int64_t kstrideA = a.npadA * 64, kstrideB = a.npadB * 64;  // bytes from one k-block to the next
+  // a panel's k-blocks (16 KB each) follow each other in memory: the data blocks, then the augmentation block
+  const int64_t panel_stride = (int64_t)nslT * PANEL_BYTES;
   const int cw = wave & 3;
   const bool copier = wave >= 4;
   const uint32_t voff0 = lane * 16 + cw * 1024;
@@ -594,8 +611,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   bool issue_live = true;       // the issue cursor still points at real work
   bool issue_on_next = false;   // ... of the tile after the one being computed
   bool issue_pending = false;   // ... and has finished that one too (see issue_one)
-  const char* pa = XbA + (int64_t)I * (TILE * 64);
-  const char* pb = XbB + (int64_t)J * (TILE * 64);
+  const char* pa = XbA + (int64_t)EJ_PANEL_A(I) * panel_stride;
+  const char* pb = XbB + (int64_t)EJ_PANEL_B(J) * panel_stride;
   const uint32_t lds_w = lds0 + cw * 1024;
   auto issue_one = [&](uint32_t Gissue) {
     if (!copier) return;
@@ -605,8 +622,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 #pragma unroll
       for (int q = 0; q < NCOPY; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, XbA, lane * 16);
     }
-    pa += kstrideA;
-    pb += kstrideB;
+    pa += PANEL_BYTES;
+    pb += PANEL_BYTES;
     if (++iks == nslT) {
       iks = 0;
       if (issue_live && issue_on_next) {
@@ -619,8 +636,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         const bool to_next = issue_live && have_next;
         issue_live = to_next;
         issue_on_next = to_next;
-        pa = XbA + (int64_t)(to_next ? In : 0) * (TILE * 64);
-        pb = XbB + (int64_t)(to_next ? Jn : 0) * (TILE * 64);
+        pa = XbA + (int64_t)(to_next ? EJ_PANEL_A(In) : 0) * panel_stride;
+        pb = XbB + (int64_t)(to_next ? EJ_PANEL_B(Jn) : 0) * panel_stride;
       }
     }
   };
@@ -728,17 +745,37 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     ++G;
   };
 
+#ifdef EJOIN_EXP_CYCLE_MARKS
+  // sections: 0 tile switch, 1 first data slice, 2 middle data slices, 3 last data slice, 4 wait + barrier of the
+  // augmentation slice, 5 its copy issue, 6 augmentation MFMAs + filter + exact path
+  unsigned long long mark_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long mark_prev = __builtin_amdgcn_s_memtime();
+#define EJ_MARK(k)                                                  \
+  {                                                                 \
+    const unsigned long long now_ = __builtin_amdgcn_s_memtime();   \
+    mark_sum[k] += now_ - mark_prev;                                \
+    mark_prev = now_;                                               \
+  }
+#else
+#define EJ_MARK(k)
+#endif
   while (have) {
     // ---------------- the nsl >= 2 data slices of the tile
+    EJ_MARK(0)
     if (copier) {
       data_slice(T_{}, F_{}, T_{});
+      EJ_MARK(1)
       for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, T_{});
+      EJ_MARK(2)
       data_slice(F_{}, T_{}, T_{});
     } else {
       data_slice(T_{}, F_{}, F_{});
+      EJ_MARK(1)
       for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, F_{});
+      EJ_MARK(2)
       data_slice(F_{}, T_{}, F_{});
     }
+    EJ_MARK(3)
     // ---------------- the augmentation slice: one step, then the filter.
     // The step adds -s_i/2 - s_j/2 to every accumulator with eight v_mfma_f32_32x32x16_f16, one per 32 x 32
     // region of the wave tile, half the matrix-core time that 32 more 16x16x32 (with 26 of 32 products zero)
@@ -755,7 +792,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
       else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
       wg_barrier();
+      EJ_MARK(4)
       issue_one(G + DIST);
+      EJ_MARK(5)
       ++G;
 #pragma unroll
       for (int mt2 = 0; mt2 < 4; ++mt2)
@@ -886,6 +925,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       if (diag) exact_path(T_{});
       else exact_path(F_{});
     }
+    EJ_MARK(6)
     // first fragments of the next tile (slice G was certified by the augmentation slice's barrier);
     // read after the filter to keep its registers free
     load_first((G % NSTAGE) * STAGE_BYTES);
@@ -904,11 +944,17 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         issue_pending = false;
         issue_live = have_next;
         issue_on_next = have_next;
-        pa = XbA + (int64_t)(have_next ? In : 0) * (TILE * 64);
-        pb = XbB + (int64_t)(have_next ? Jn : 0) * (TILE * 64);
+        pa = XbA + (int64_t)(have_next ? EJ_PANEL_A(In) : 0) * panel_stride;
+        pb = XbB + (int64_t)(have_next ? EJ_PANEL_B(Jn) : 0) * panel_stride;
       }
     }
   }
+#ifdef EJOIN_EXP_CYCLE_MARKS
+  if (lane == 0 && !COUNT && a.capacity >= 16) {
+    unsigned long long* out = reinterpret_cast<unsigned long long*>(a.pairs) + (a.capacity - 16) + 8 * (wave >> 2);
+    for (int k = 0; k < 8; ++k) atomicAdd(out + k, mark_sum[k]);
+  }
+#endif
   xcd_leave();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the dump copies must land before the wave ends
   if (!COUNT) flush();
@@ -1068,19 +1114,20 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
   const int64_t npad = pad_rows(n);
   const int64_t waves = ((Xp ? npad : n) + 15) / 16;
   const dim3 grid((unsigned)((waves + 3) / 4));
-  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp);
-  else hipLaunchKernelGGL(k_norms<false>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp);
+  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, k_blocks(d) + 1);
+  else hipLaunchKernelGGL(k_norms<false>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, 0);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
 
 // Augmentation rows of one set from its norms and the running maximum of all norms.
-// aug: where the join wants the set's augmentation k-block (null for the dense-tile call);
-// counter / counts: what the kernel clears on the way (may be null).
-int launch_aux(ejoin_ctx* ctx, uint32_t* status, const float* s, int64_t n, uint4* H, uint4* aug, unsigned long long* counter,
-               uint32_t* counts, hipStream_t st) {
+// Xp: the set's packed copy, whose panels get their augmentation k-block (k-block number `data_blocks`, behind the
+// data blocks; null for the dense-tile call); counter / counts: what the kernel clears on the way (may be null).
+int launch_aux(ejoin_ctx* ctx, uint32_t* status, const float* s, int64_t n, uint4* H, uint4* Xp, int data_blocks,
+               unsigned long long* counter, uint32_t* counts, hipStream_t st) {
   const int64_t npad = pad_rows(n);
-  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, s, n, npad, status, H, aug, counter, counts);
+  hipLaunchKernelGGL(k_aux, dim3((unsigned)(npad / 256)), dim3(256), 0, st, s, n, npad, status, H, Xp, data_blocks, data_blocks + 1, counter,
+                     counts);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
 }
@@ -1138,8 +1185,6 @@ int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, 
   memset(&a, 0, sizeof(a));
   a.XpA = A.Xp;
   a.XpB = B.Xp;
-  a.npadA = A.pad;
-  a.npadB = B.pad;
   a.nA = A.n;
   a.nB = B.n;
   a.self = self ? 1 : 0;
@@ -1196,8 +1241,8 @@ int run_join(ejoin_ctx* ctx, const Workspace& w, bool own, const uint16_t* XA, i
   EJ_RC(launch_norms(ctx, XA, nA, d, ldA, sA, w.status + 1, XpA, st));
   if (!self) EJ_RC(launch_norms(ctx, XB, nB, d, ldB, sB, w.status + 1, XpB, st));
   // the augmentation rows need the maximum over both sets, so they follow both norm kernels
-  EJ_RC(launch_aux(ctx, w.status, sA, nA, HA, XpA + (int64_t)nkb * padA * 4, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
-  if (!self) EJ_RC(launch_aux(ctx, w.status, sB, nB, HB, XpB + (int64_t)nkb * padB * 4, nullptr, COUNT ? r.counts_b : nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, sA, nA, HA, XpA, nkb, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
+  if (!self) EJ_RC(launch_aux(ctx, w.status, sB, nB, HB, XpB, nkb, nullptr, COUNT ? r.counts_b : nullptr, st));
   const Operand A{XpA, nA, padA}, B{self ? XpA : XpB, self ? nA : nB, self ? padA : padB};
   return launch_join<COUNT>(ctx, w, own, A, B, self, nkb, eps, r, st);
 }
@@ -1220,8 +1265,8 @@ int run_join_split(ejoin_ctx* ctx, const float* X32, int64_t n, int32_t d, int64
     hipLaunchKernelGGL(k_norms_packed, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, XpA, XpB, n, pad, 3 * nkb, w.s, w.status + 1);
     EJ_TRY(hipGetLastError());
   }
-  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, XpA + (int64_t)3 * nkb * pad * 4, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
-  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, XpB + (int64_t)3 * nkb * pad * 4, nullptr, nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, XpA, 3 * nkb, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, XpB, 3 * nkb, nullptr, nullptr, st));
   const Operand A{XpA, n, pad}, B{XpB, n, pad};
   return launch_join<COUNT>(ctx, w, true, A, B, true, 3 * nkb, eps, r, st);
 }
@@ -1240,8 +1285,8 @@ int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, in
   hipLaunchKernelGGL(k_merge_max, dim3(1), dim3(64), 0, st, w.status + 1, P->max_bits);
   EJ_TRY(hipGetLastError());
   // the augmentation rows of both sets are scaled to the largest norm of the two: those of the prepared set are rewritten
-  EJ_RC(launch_aux(ctx, w.status, P->s, P->n, P->H, P->Xp + (int64_t)nkb * P->pad * 4, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
-  EJ_RC(launch_aux(ctx, w.status, w.s, nQ, w.H, w.Xp + (int64_t)nkb * padQ * 4, nullptr, COUNT ? r.counts_b : nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, P->s, P->n, P->H, P->Xp, nkb, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, nQ, w.H, w.Xp, nkb, nullptr, COUNT ? r.counts_b : nullptr, st));
   const Operand A{P->Xp, P->n, P->pad}, B{w.Xp, nQ, padQ};
   return launch_join<COUNT>(ctx, w, true, A, B, false, nkb, eps, r, st);
 }
@@ -1527,7 +1572,7 @@ int ejoin_dist2_tile(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, in
   hipStream_t st = static_cast<hipStream_t>(stream);
   EJ_RC(begin_call(ctx, w, true, st));  // (no join kernel follows: the status block stays marked for a reset)
   EJ_RC(launch_norms(ctx, X, n, d, ld, w.s, w.status + 1, nullptr, st));
-  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, nullptr, nullptr, nullptr, st));
+  EJ_RC(launch_aux(ctx, w.status, w.s, n, w.H, nullptr, 0, nullptr, nullptr, st));
   hipLaunchKernelGGL(k_dist2_tile, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(64), 0, st, X, w.H, w.status, n, ld, k_blocks(d), i0, j0, rows, cols, out);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
