@@ -108,6 +108,21 @@ int ejoin_selfjoin_count(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
 int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
                          uint32_t* pairs, float* dist2, uint64_t capacity, uint64_t* n_pairs, void* stream);
 
+/* The self-join with its result returned to host memory in batches, for the end-to-end response time the paper
+ * measures (Section 4.1: all overheads included, "storing the results in main memory"; result sets are returned
+ * from the GPU to the host in batches).  The join is cut into `batches` launches (at most EJOIN_MAX_BATCHES; by rows
+ * of 4096 x 4096-point blocks of the distance matrix, about the same work each); while launch b + 1 computes, the
+ * pairs launch b found are copied to the host on a second stream.  Unlike the other calls this one BLOCKS: it
+ * returns when every pair is in host memory.
+ *   pairs, dist2    (device, capacity x 2 x u32 / capacity x f32 or NULL): where the kernels collect the result
+ *   host_pairs, host_dist2 (HOST, same sizes; pinned memory for full copy speed; host_dist2 NULL iff dist2 NULL)
+ *   *host_n_pairs   (HOST): number of pairs FOUND; if it exceeds capacity, exactly capacity pairs were returned
+ * Result set and conventions otherwise as ejoin_selfjoin_pairs (same pairs, in another order). */
+#define EJOIN_MAX_BATCHES 32
+int ejoin_selfjoin_pairs_to_host(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps,
+                                 uint32_t* pairs, float* dist2, uint64_t capacity, int32_t batches,
+                                 uint32_t* host_pairs, float* host_dist2, uint64_t* host_n_pairs, void* stream);
+
 /* For callers that cannot allocate device memory while they run -- code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc: ejoin_selfjoin_pairs with the workspace taken from a
  * static device array of EJOIN_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU

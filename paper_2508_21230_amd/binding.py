@@ -48,6 +48,8 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.ejoin_selfjoin_count.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, vp]
     lib.ejoin_selfjoin_pairs.restype = C.c_int
     lib.ejoin_selfjoin_pairs.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
+    lib.ejoin_selfjoin_pairs_to_host.restype = C.c_int
+    lib.ejoin_selfjoin_pairs_to_host.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, i32, vp, vp, C.POINTER(u64), vp]
     lib.ejoin_selfjoin_pairs_noalloc.restype = C.c_int
     lib.ejoin_selfjoin_pairs_noalloc.argtypes = [vp, vp, i64, i32, i64, f32, vp, vp, u64, vp, vp]
     lib.ejoin_selfjoin_count_f32.restype = C.c_int
@@ -192,6 +194,24 @@ class EJoin:
                                                    dist2.data_ptr() if dist2 is not None else None, capacity,
                                                    n_pairs.data_ptr(), self._stream()), self._h)
         return pairs, dist2, n_pairs
+
+    def selfjoin_pairs_to_host(self, X: torch.Tensor, eps: float, batches: int, pairs: torch.Tensor, dist2: torch.Tensor | None,
+                               host_pairs: torch.Tensor, host_dist2: torch.Tensor | None, d: int | None = None) -> int:
+        """ejoin_selfjoin_pairs_to_host: the join in `batches` launches, each batch's pairs copied to the host tensors
+        (CPU, ideally pinned: int32[capacity, 2], float32[capacity] or None) while the next one computes.  Blocks;
+        returns the number of pairs found."""
+        n, d, ld = self._x(X, d)
+        capacity = int(pairs.shape[0])
+        if host_pairs.is_cuda or host_pairs.shape[0] < capacity or not host_pairs.is_contiguous():
+            raise EJoinError("host_pairs must be a contiguous CPU tensor of at least `capacity` pairs")
+        if (dist2 is None) != (host_dist2 is None):
+            raise EJoinError("dist2 and host_dist2 go together")
+        found = C.c_uint64()
+        self._check(self._lib.ejoin_selfjoin_pairs_to_host(self._h, X.data_ptr(), n, d, ld, float(eps), pairs.data_ptr(),
+                                                           dist2.data_ptr() if dist2 is not None else None, capacity, int(batches),
+                                                           host_pairs.data_ptr(), host_dist2.data_ptr() if host_dist2 is not None else None,
+                                                           C.byref(found), self._stream()), self._h)
+        return int(found.value)
 
     def selfjoin_pairs_noalloc(self, X: torch.Tensor, eps: float, pairs: torch.Tensor, dist2: torch.Tensor | None,
                                n_pairs: torch.Tensor, d: int | None = None):

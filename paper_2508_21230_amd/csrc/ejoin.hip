@@ -80,6 +80,7 @@ struct JoinArgs {
   int nslices;  // roundup(d, 64) / 32 : k-blocks of data (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntilesA, ntilesB;  // ceil(n / TILE)
+  uint32_t sb_row_begin, sb_row_end;  // rows of super-blocks this launch covers (a join returned in batches is cut by them)
   // pair mode
   uint32_t* pairs;
   float* dist2;
@@ -589,7 +590,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 
   // ---------------- prologue
   TileCursor tc;
-  tc.init(blockIdx.x, gridDim.x, (uint32_t)a.self, a.ntilesA, a.ntilesB);
+  tc.init(blockIdx.x, gridDim.x, (uint32_t)a.self, a.ntilesA, a.ntilesB, a.sb_row_begin, a.sb_row_end);
   uint32_t I = 0, J = 0, In = 0, Jn = 0;
   bool have = tc.next(I, J);
   // a workgroup that leaves (now, or after its last tile) releases every later alignment of its XCD
@@ -998,6 +999,11 @@ struct ejoin_ctx {
   int profiling;
   hipEvent_t ev[4];
   int ev_valid;
+  // batched result return (ejoin_selfjoin_pairs_to_host): a stream for the device-to-host copies, one event per
+  // batch and the pair counter's value after each batch (pinned host memory)
+  hipStream_t copy_stream;
+  hipEvent_t batch_ev[EJOIN_MAX_BATCHES];
+  unsigned long long* batch_count;
   char hip_error[256];
 };
 
@@ -1180,7 +1186,7 @@ int begin_call(ejoin_ctx* ctx, const Workspace& w, bool own, hipStream_t st) {
 // The join kernel on two packed operand sets whose augmentation blocks are in place.
 template <bool COUNT>
 int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, const Operand& B, bool self, int nslices, float eps,
-                const Results& r, hipStream_t st) {
+                const Results& r, hipStream_t st, uint32_t sb_row_begin = 0, uint32_t sb_row_end = 0xFFFFFFFFu) {
   JoinArgs a;
   memset(&a, 0, sizeof(a));
   a.XpA = A.Xp;
@@ -1193,6 +1199,8 @@ int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, 
   a.thr = -0.5f * (eps * eps);
   a.ntilesA = (uint32_t)(A.pad / TILE);
   a.ntilesB = (uint32_t)(B.pad / TILE);
+  a.sb_row_begin = sb_row_begin;
+  a.sb_row_end = sb_row_end;
   a.pairs = r.pairs;
   a.dist2 = r.dist2;
   a.capacity = r.capacity;
@@ -1225,9 +1233,13 @@ int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, 
 }
 
 // Join of FP16 rows in workspace w (the context's own, or a carving of the static scratch).  XB == nullptr: self-join of XA.
+// batch_rows (self-join, pair mode only): null, or nbatches + 1 ascending bounds in rows of super-blocks; the join kernel is
+// then launched once per range, and after each launch the pair counter is copied to ctx->batch_count[b] and
+// ctx->batch_ev[b] recorded (the counter runs on from launch to launch: the pairs of batch b are those between the
+// counts of batch b - 1 and b).
 template <bool COUNT>
 int run_join(ejoin_ctx* ctx, const Workspace& w, bool own, const uint16_t* XA, int64_t nA, int64_t ldA, const uint16_t* XB, int64_t nB,
-             int64_t ldB, int32_t d, float eps, const Results& r, hipStream_t st) {
+             int64_t ldB, int32_t d, float eps, const Results& r, hipStream_t st, const uint32_t* batch_rows = nullptr, int nbatches = 0) {
   const bool self = (XB == nullptr);
   const int64_t padA = pad_rows(nA), padB = self ? 0 : pad_rows(nB);
   const int nkb = k_blocks(d);
@@ -1244,7 +1256,17 @@ int run_join(ejoin_ctx* ctx, const Workspace& w, bool own, const uint16_t* XA, i
   EJ_RC(launch_aux(ctx, w.status, sA, nA, HA, XpA, nkb, r.counter(COUNT), COUNT ? r.counts : nullptr, st));
   if (!self) EJ_RC(launch_aux(ctx, w.status, sB, nB, HB, XpB, nkb, nullptr, COUNT ? r.counts_b : nullptr, st));
   const Operand A{XpA, nA, padA}, B{self ? XpA : XpB, self ? nA : nB, self ? padA : padB};
-  return launch_join<COUNT>(ctx, w, own, A, B, self, nkb, eps, r, st);
+  if (!batch_rows) return launch_join<COUNT>(ctx, w, own, A, B, self, nkb, eps, r, st);
+  for (int b = 0; b < nbatches; ++b) {
+    if (b > 0) {  // the XCD alignment counters start every launch from zero
+      hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, w.status + 8, (int64_t)NUM_XCD, 0u);
+      EJ_TRY(hipGetLastError());
+    }
+    EJ_RC(launch_join<COUNT>(ctx, w, own, A, B, self, nkb, eps, r, st, batch_rows[b], batch_rows[b + 1]));
+    EJ_TRY(hipMemcpyAsync(ctx->batch_count + b, r.n_pairs, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    EJ_TRY(hipEventRecord(ctx->batch_ev[b], st));
+  }
+  return EJOIN_OK;
 }
 
 // Split-FP16 self-join of FP32 rows (see k_split_pack): the same join kernel on 3 * nkb k-blocks.
@@ -1365,6 +1387,9 @@ int ejoin_create(ejoin_ctx** out, int device) {
   // this device's copy of the static scratch (the device is current here)
   if (e == hipSuccess) e = hipGetSymbolAddress(reinterpret_cast<void**>(&ctx->static_scratch), HIP_SYMBOL(scratch));
   for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&ctx->ev[i]);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking);
+  for (int i = 0; i < EJOIN_MAX_BATCHES && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ctx->batch_ev[i], hipEventDisableTiming);
+  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->batch_count), EJOIN_MAX_BATCHES * sizeof(unsigned long long), hipHostMallocDefault);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (e != hipSuccess) {
@@ -1386,6 +1411,10 @@ int ejoin_destroy(ejoin_ctx* ctx) {
   if (ctx->ws.Xp) (void)hipFree(ctx->ws.Xp);
   for (int i = 0; i < 4; ++i)
     if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
+  for (int i = 0; i < EJOIN_MAX_BATCHES; ++i)
+    if (ctx->batch_ev[i]) (void)hipEventDestroy(ctx->batch_ev[i]);
+  if (ctx->copy_stream) (void)hipStreamDestroy(ctx->copy_stream);
+  if (ctx->batch_count) (void)hipHostFree(ctx->batch_count);
   delete ctx;
   return EJOIN_OK;
 }
@@ -1431,6 +1460,56 @@ int ejoin_selfjoin_pairs(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d
   EJ_RC(check_common(ctx, X, n, d, ld));
   EJ_RC(check_pairs_out(pairs, capacity, n_pairs, eps));
   return join_on_ctx<false>(ctx, X, n, ld, nullptr, 0, 0, d, eps, pair_results(pairs, dist2, capacity, n_pairs), stream);
+}
+
+int ejoin_selfjoin_pairs_to_host(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs,
+                                 float* dist2, uint64_t capacity, int32_t batches, uint32_t* host_pairs, float* host_dist2,
+                                 uint64_t* host_n_pairs, void* stream) {
+  EJ_RC(check_common(ctx, X, n, d, ld));
+  if (!pairs || !host_pairs || !host_n_pairs || capacity == 0 || bad_eps(eps) || batches < 1 || (dist2 == nullptr) != (host_dist2 == nullptr))
+    return EJOIN_EINVAL;
+  DeviceGuard guard(ctx->device);
+  if (!guard.ok) return EJOIN_EHIP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // Ranges of super-block rows with about the same number of tiles each (row P of the triangle holds nsb - P super-blocks).
+  const uint32_t nsb = (uint32_t)((pad_rows(n) / TILE + SB - 1) / SB);
+  int nb = batches > EJOIN_MAX_BATCHES ? EJOIN_MAX_BATCHES : batches;
+  if ((uint32_t)nb > nsb) nb = (int)nsb;
+#ifdef EJOIN_ABL_ROWMAJOR_TILES
+  nb = 1;  // (this ablation build deals the whole grid out in one launch)
+#endif
+  uint32_t bounds[EJOIN_MAX_BATCHES + 1];
+  {
+    const double total = 0.5 * nsb * (nsb + 1.0);
+    double done = 0;
+    uint32_t P = 0;
+    bounds[0] = 0;
+    for (int b = 1; b < nb; ++b) {
+      while (P < nsb && done < total * b / nb) done += nsb - P++;
+      if (P <= bounds[b - 1]) P = bounds[b - 1] + 1;  // every batch gets at least one row
+      bounds[b] = P;
+    }
+    bounds[nb] = 0xFFFFFFFFu;
+  }
+  // the counter lives in the context's status block (the caller gets the final count in host memory)
+  uint64_t* counter = reinterpret_cast<uint64_t*>(ctx->ws.status + 32);
+  EJ_RC(ensure_workspace(ctx, pad_rows(n), pad_dims(d)));
+  EJ_RC(run_join<false>(ctx, ctx->ws, true, X, n, ld, nullptr, 0, 0, d, eps, pair_results(pairs, dist2, capacity, counter), st, bounds, nb));
+  // As each batch completes, its pairs go to the host on the copy stream while the next batch computes.
+  unsigned long long lo = 0;
+  for (int b = 0; b < nb; ++b) {
+    EJ_TRY(hipEventSynchronize(ctx->batch_ev[b]));
+    unsigned long long hi = ctx->batch_count[b];
+    if (hi > capacity) hi = capacity;
+    if (hi > lo) {
+      EJ_TRY(hipMemcpyAsync(host_pairs + 2 * lo, pairs + 2 * lo, (hi - lo) * 2 * sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->copy_stream));
+      if (dist2) EJ_TRY(hipMemcpyAsync(host_dist2 + lo, dist2 + lo, (hi - lo) * sizeof(float), hipMemcpyDeviceToHost, ctx->copy_stream));
+      lo = hi;
+    }
+  }
+  EJ_TRY(hipStreamSynchronize(ctx->copy_stream));
+  *host_n_pairs = ctx->batch_count[nb - 1];
+  return EJOIN_OK;
 }
 
 int ejoin_selfjoin_pairs_noalloc(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_t ld, float eps, uint32_t* pairs,

@@ -42,8 +42,11 @@ struct TileCursor {
   uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
   uint32_t fast_left;    // complete super-blocks that follow the current one in its row (see next)
   uint32_t start, stride;  // (row-major ablation only) first tile and stride of this workgroup
-  // self_join: upper triangle of an nt x nt grid (nt_a == nt_b); otherwise the whole nt_a x nt_b grid
-  EJ_HD void init(uint32_t block, uint32_t nblocks, uint32_t self_join, uint32_t nt_a, uint32_t nt_b) {
+  // self_join: upper triangle of an nt x nt grid (nt_a == nt_b); otherwise the whole nt_a x nt_b grid.
+  // sb_row_begin .. sb_row_end - 1: the rows of super-blocks this launch covers (a join may be cut into several
+  // launches by rows of super-blocks; 0 .. UINT32_MAX = everything)
+  EJ_HD void init(uint32_t block, uint32_t nblocks, uint32_t self_join, uint32_t nt_a, uint32_t nt_b, uint32_t sb_row_begin = 0,
+                  uint32_t sb_row_end = 0xFFFFFFFFu) {
     start = block;
     stride = 0;
     xcd = block % EJ_NUM_XCD;
@@ -53,8 +56,11 @@ struct TileCursor {
     ntB = nt_b;
     nsbA = (nt_a + EJ_SB - 1) / EJ_SB;
     nsbB = (nt_b + EJ_SB - 1) / EJ_SB;
+    if (sb_row_end < nsbA) nsbA = sb_row_end;  // (the rows past the range are simply not enumerated)
     rem = block / EJ_NUM_XCD;
-    P = Q = sbi = 0;
+    P = sb_row_begin;
+    Q = self_join ? sb_row_begin : 0;
+    sbi = 0;
     fast_left = 0;
 #ifdef EJOIN_ABL_ROWMAJOR_TILES
     stride = nblocks;

@@ -441,3 +441,61 @@ def test_contexts_and_prepared_sets_release_their_device_memory():
     torch.cuda.synchronize()
     free1 = torch.cuda.mem_get_info()[0]
     assert free0 - free1 < 64 << 20, f"device memory not returned: {free0 - free1} bytes"
+
+
+@pytest.mark.parametrize("batches", [1, 3, 32])
+def test_batched_return_to_host_gives_the_pairs_of_the_plain_join(ej, batches):
+    """ejoin_selfjoin_pairs_to_host: the join cut into launches by rows of super-blocks, each batch copied to pinned host
+    memory while the next computes -- same pair set and squared distances as ejoin_selfjoin_pairs, also when the
+    buffer overflows (exactly `capacity` pairs returned, the count still complete)."""
+    n = 21_000  # 83 tiles per side: six rows of super-blocks
+    X = datagen.generate(2, n=n)
+    Xd = torch.from_numpy(X.view(np.int16)).cuda()
+    eps = 0.78
+    want_pairs, want_d2, want_n = ej.selfjoin_pairs(Xd, eps, capacity=4_000_000)
+    torch.cuda.synchronize()
+    wp, wd, found = parity.to_host_pairs(want_pairs, want_d2, want_n)
+    assert n < found < 4_000_000
+    cap = found + 100
+    pairs = torch.empty((cap, 2), dtype=torch.int32, device="cuda")
+    d2 = torch.empty(cap, dtype=torch.float32, device="cuda")
+    hp = torch.empty((cap, 2), dtype=torch.int32).pin_memory()
+    hd = torch.empty(cap, dtype=torch.float32).pin_memory()
+    got = ej.selfjoin_pairs_to_host(Xd, eps, batches, pairs, d2, hp, hd)
+    assert got == found
+    assert ej.status() == 0
+    gp = hp[:got].numpy().view(np.uint32)
+    ko, kg = orc.pair_keys(wp), orc.pair_keys(gp)
+    oo, og = np.argsort(ko), np.argsort(kg)
+    assert np.array_equal(ko[oo], kg[og])
+    assert np.array_equal(wd[oo].view(np.uint32), hd[:got].numpy()[og].view(np.uint32))
+    # overflow: a buffer of half the size
+    small = found // 2
+    got2 = ej.selfjoin_pairs_to_host(Xd, eps, batches, pairs[:small], d2[:small], hp[:small], hd[:small])
+    assert got2 == found
+    sub = orc.pair_keys(hp[:small].numpy().view(np.uint32))
+    assert np.unique(sub).size == small and np.isin(sub, ko).all()
+
+
+def test_status_waits_for_the_stream_of_the_call(ej):
+    """ejoin_status must order against the stream the join ran on, also a non-blocking side stream that the null
+    stream does not wait for: a join over data with an Inf, queued behind other work on such a stream, then status()
+    with no device synchronisation in between."""
+    n, d = 30_000, 128
+    good = torch.from_numpy(datagen.generate(2, n=n).view(np.int16)).cuda()
+    bad = good.clone()
+    bad[7, 3] = 0x7C00  # +Inf
+    ej.selfjoin_count(good, 0.5)
+    torch.cuda.synchronize()
+    assert ej.status() == 0
+    side = torch.cuda.Stream()
+    a = torch.randn(4096, 4096, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(20):  # tens of milliseconds of work ahead of the join
+            a = a @ a * 1e-3
+        counts, total = ej.selfjoin_count(bad, 0.5)
+        st = ej.status()
+    assert st == 2
+    torch.cuda.synchronize()
+    assert int(total.cpu()[0]) == 0

@@ -23,13 +23,21 @@ def build_schedule(tmp_path_factory, kind):
     lib = ctypes.CDLL(str(out))
     lib.ejoin_test_schedule.restype = ctypes.c_int64
     lib.ejoin_test_schedule.argtypes = [ctypes.c_uint32] * 4 + [ctypes.c_void_p, ctypes.c_int64]
+    lib.ejoin_test_schedule_rows.restype = ctypes.c_int64
+    lib.ejoin_test_schedule_rows.argtypes = [ctypes.c_uint32] * 6 + [ctypes.c_void_p, ctypes.c_int64]
 
     def run(nblocks, self_join, nt_a, nt_b):
         want = nt_a * (nt_a + 1) // 2 if self_join else nt_a * nt_b
         buf = np.zeros((want + 8, 4), dtype=np.uint32)
         m = lib.ejoin_test_schedule(nblocks, int(self_join), nt_a, nt_b, buf.ctypes.data, want + 8)
         return buf[:min(m, want + 8)], m, want
+    def run_rows(nblocks, self_join, nt_a, nt_b, row_begin, row_end):
+        want = nt_a * (nt_a + 1) // 2 if self_join else nt_a * nt_b
+        buf = np.zeros((want + 8, 4), dtype=np.uint32)
+        m = lib.ejoin_test_schedule_rows(nblocks, int(self_join), nt_a, nt_b, row_begin, row_end, buf.ctypes.data, want + 8)
+        return buf[:min(m, want + 8)], m
     run.kind = kind
+    run.rows = run_rows
     return run
 
 
@@ -94,3 +102,23 @@ def test_fast_step_gives_the_same_sequence_as_the_general_step(tmp_path_factory,
     b, mb, _ = slow(nblocks, self_join, nt_a, nt_b)
     assert ma == mb == want
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("self_join,nt_a,nt_b,cuts", [(True, 100, 100, (0, 2, 3, 7)), (True, 391, 391, (0, 5, 11, 18, 25)), (False, 50, 77, (0, 1, 4)),
+                                                     (True, 17, 17, (0, 1, 2)), (True, 40, 40, (0, 9))])
+def test_launches_cut_by_rows_of_super_blocks_cover_every_tile_once(sched, self_join, nt_a, nt_b, cuts):
+    """A join returned in batches runs one launch per range of super-block rows: the ranges' tiles are disjoint and
+    together are all the tiles."""
+    if sched.kind != "xcd_rectangles":
+        pytest.skip("the row-major ablation enumerates the whole grid in one launch")
+    want = nt_a * (nt_a + 1) // 2 if self_join else nt_a * nt_b
+    bounds = list(cuts) + [0xFFFFFFFF]
+    keys = []
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        tiles, m = sched.rows(256, self_join, nt_a, nt_b, lo, hi)
+        I, J = tiles[:, 2].astype(np.int64), tiles[:, 3].astype(np.int64)
+        assert m == len(tiles)
+        assert ((I // 16 >= lo) & (I // 16 < hi)).all()
+        keys.append(I * (nt_b + 1) + J)
+    keys = np.concatenate(keys)
+    assert keys.size == want and np.unique(keys).size == want
