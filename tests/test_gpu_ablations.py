@@ -37,6 +37,9 @@ def test_ablation_variant_passes_the_parity_rule(name, oracle_results):
     path = os.path.join(build.ABLATION_DIR, f"libejoin_{name}.so")
     if not os.path.exists(path):
         pytest.skip(f"{path} is not built (python -m paper_2508_21230_amd.build --ablations)")
+    sources = [build.SRC, os.path.join(os.path.dirname(build.SRC), "tile_cursor.h"), os.path.join(os.path.dirname(build.SRC), "panel_layout.h")]
+    if os.path.getmtime(path) < max(os.path.getmtime(f) for f in sources):
+        pytest.skip(f"{path} is older than the kernel source: rebuild the variants")
     ej = pkg.EJoin(0, lib_path=path)
     try:
         for X, P, eps, opairs, od2 in oracle_results:
