@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Writes the per-workload accuracy record of the HIP path at the full sizes of the five workloads.
 
-    python tests/parity_full_size_record.py [--rows 2048] [--out gpurun_out/parity_full_size.md]
+    python tests/parity_full_size_record.py [--rows 2048] [--out parity_full_size.md]
 
 For each workload and selectivity: the GPU self-join (pair list with squared distances) against the CPU oracle
 under the strict parity rule (tests/fullsize.py), and what the paper reports about its own accuracy:
@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--rows", type=int, default=2048, help="seeded query rows per workload for workloads 3-5")
-    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "parity_full_size.md"))
+    ap.add_argument("--out", default="parity_full_size.md", help="where the table is written (it is kept under profiles/)")
     ap.add_argument("--workloads", default="1,2,3,4,5")
     args = ap.parse_args()
 
@@ -67,7 +67,8 @@ def main():
             f"{st.get('floor_used', 0)} | {st['overlap_accuracy']:.6f} | {st.get('dist_err_mean', 0):.2e} | {st.get('dist_err_std', 0):.2e} |")
     lines += ["", "Whole-output properties checked on every run above: i <= j, indices < n, no duplicate pair, all n self pairs present,",
               "count mode equals the histogram of the pair list and its total the number of pairs.", ""]
-    os.makedirs(os.path.dirname(args.out), exist_ok=True)
+    if os.path.dirname(args.out):
+        os.makedirs(os.path.dirname(args.out), exist_ok=True)
     with open(args.out, "w") as f:
         f.write("\n".join(lines))
     print("\n".join(lines))
