@@ -141,8 +141,9 @@ def experiments(args):
 
     with open(os.path.join(ROOT, "paper_2508_21230_amd", "workloads_eps.json")) as f:
         eps_all = json.load(f)
-    sections = ["tile switch (cursor, first fragments)", "first data slice", "middle data slices", "last data slice",
-                "augmentation slice: wait + barrier", "augmentation slice: copy issue", "augmentation MFMAs + filter + exact path"]
+    sections = ["tile cursor", "first slice", "middle slices", "last slice", "augmentation MFMAs + filter + exact path",
+                "first fragments of the next tile (the mark waits for them: their latency)", "periodic re-alignment of the XCD's workgroups",
+                "wait for the copies in flight before a re-alignment"]
     for w in [int(x) for x in args.workloads.split(",")]:
         spec = datagen.WORKLOADS[w]
         n, d, S = args.n or spec["n"], spec["d"], spec["selectivity"][0]
@@ -182,8 +183,8 @@ def experiments(args):
         torch.cuda.synchronize()
         v = marks.cpu().numpy().astype(float) / (4.0 * tiles)  # 4 wavefronts of each kind per workgroup, tiles / 256 tiles per workgroup, 256 workgroups
         rec = {"experiment": "cycle_marks", "workload": w, "n": n, "d": d, "join_ms": ms, "unit": "s_memtime ticks per tile and wavefront",
-               "waves_0_3_no_copies": {sections[k]: round(v[k], 1) for k in range(7)}, "waves_4_7_copying": {sections[k]: round(v[8 + k], 1) for k in range(7)},
-               "ticks_per_tile": round(v[:8].sum(), 1), "mfma_ticks_if_busy": "1024 cycles per data slice and SIMD, 512 for the augmentation step"}
+               "waves_0_3_no_copies": {sections[k]: round(v[k], 1) for k in range(8)}, "waves_4_7_copying": {sections[k]: round(v[8 + k], 1) for k in range(8)},
+               "ticks_per_tile": round(v[:8].sum(), 1), "mfma_ticks_if_busy": "1024 cycles per slice and SIMD, 512 for the augmentation step"}
         print(json.dumps(rec), flush=True)
         ej.close()
         del pairs, d2, Xd

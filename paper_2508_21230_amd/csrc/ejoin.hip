@@ -59,7 +59,15 @@ constexpr int SB = (int)EJ_SB;
 constexpr int PANEL_BYTES = TILE * KSLICE * 2;  // 16 KB : one operand panel of one stage
 constexpr int STAGE_BYTES = 2 * PANEL_BYTES;    // A panel + B panel
 constexpr int DUMP_OFF = NSTAGE * STAGE_BYTES;  // 1 KB that absorbs the copies issued past the end of the work
-constexpr int STG_OFF = DUMP_OFF + 1024;        // per-wave result staging: STG_CAP entries of (i, j, d2)
+// Operands of the augmentation step of the tile being computed (see k_aux): 16 bytes per row of the A panel (4 KB),
+// then 16 bytes per column of the B panel (4 KB); and the two constant chunks { C, 0 } and { 0, C } of that step,
+// repeated every 512 bytes (so that "region t" is the same address step for every lane of an operand read)
+constexpr int AUG_OFF = DUMP_OFF + 1024;
+constexpr int AUG_PART_BYTES = TILE * 16;
+constexpr int AUGC_OFF = AUG_OFF + 2 * AUG_PART_BYTES;
+constexpr int AUG_REGION_STEP = 32 * 16;        // 32 rows of 16 bytes
+constexpr int AUGC_BYTES = 4 * AUG_REGION_STEP;
+constexpr int STG_OFF = AUGC_OFF + AUGC_BYTES;  // per-wave result staging: STG_CAP entries of (i, j, d2)
 constexpr int STG_CAP = 128;
 constexpr int STG_WAVE_BYTES = STG_CAP * 12;
 constexpr int LDS_BYTES = STG_OFF + 8 * STG_WAVE_BYTES;
@@ -77,7 +85,7 @@ struct JoinArgs {
   int64_t nA, nB;
   int self;                // 1: self-join (upper triangle, self pairs), 0: two different sets (full rectangle)
   uint32_t* status;        // status block of the workspace (see k_reset)
-  int nslices;  // roundup(d, 64) / 32 : k-blocks of data (the augmentation block follows them)
+  int nslices;  // k-blocks of data per panel = slices per tile, at least DIST (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntilesA, ntilesB;  // ceil(n / TILE)
   uint32_t sb_row_begin, sb_row_end;  // rows of super-blocks this launch covers (a join returned in batches is cut by them)
@@ -99,6 +107,7 @@ struct JoinArgs {
 // Small kernels
 // ------------------------------------------------------------------------------------------
 // Status block of a workspace (64 words): [0] status word, [1] largest norm seen so far in the call (FP32 bits),
+// [2..3] the constant C = { c, c, c, 0 } of the call's augmentation step (FP16 bits, written by k_aux),
 // [8..15] alignment counters of the XCDs.  Between calls [1] and [8..15] are zero: k_aux clears the counters
 // (and the result counter of the call), k_join clears the maximum.  k_reset restores that state after a call
 // that did not get as far as its join kernel, and before every call on the shared static workspace.
@@ -137,7 +146,8 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 template <bool PACK>
 __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int k32steps,
                                                float* __restrict__ s, uint32_t* __restrict__ max_bits, uint4* __restrict__ Xp,
-                                               int blocks /* k-blocks per panel of Xp: k32steps + 1 */) {
+                                               int blocks /* k-blocks per panel of Xp: the k32steps data blocks, zero blocks
+                                                              up to the join kernel's minimum, the augmentation block */) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t row0 = blk * 16;
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   int64_t at = 0;
   if (PACK) at = place_of(row_own, lane >> 4);
   if (PACK && row0 >= n) {  // padding rows only
-    for (int k = 0; k < k32steps; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
+    for (int k = 0; k < blocks - 1; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
     return;
   }
   const bool valid = row_own < n;
@@ -158,6 +168,8 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, a, acc, 0, 0, 0);
     if (PACK) Xp[packed_index(at, k, blocks)] = valid ? __builtin_bit_cast(uint4, a) : make_uint4(0, 0, 0, 0);
   }
+  if (PACK)
+    for (int k = k32steps; k < blocks - 1; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
   // element (row, col) of the 16 x 16 block sits in lane col + 16 * (row / 4), register row % 4
   const int c = lane & 15, g = lane >> 4;
   uint32_t bits = 0;
@@ -197,9 +209,11 @@ constexpr uint32_t P1_OUT_OF_RANGE = 0xFB53u;  // -60000 in FP16
 // 16-byte row is  H_i = { P_i, C } = { p1, p2, p3, 0, c, c, c, 0 }; the extra step multiplies
 // pieces by constants, c (p1 + p2 + p3)_i + c (q1 + q2 + q3)_j = -s_i/2 - s_j/2, every product exact in FP32.
 // H (npad rows) serves the dense-tile kernel.  For the join the operands of the extra step are also
-// written, ready made, as one more k-block behind the data k-blocks of each panel of the packed set (`Xp`,
-// may be null; k-block `aug_kb` of `blocks`), so that the join kernel streams them through the same LDS
-// stages as the data (layout: panel_layout.h, "the augmentation step").
+// written, ready made, into one more k-block behind the data k-blocks of each panel of the packed set (`Xp`,
+// may be null; k-block `aug_kb` of `blocks`): 16 bytes per row for the panel as the A operand (chunk 0 of
+// panel_layout.h, "the augmentation step": 256 x 16 B), then 16 bytes per row for the panel as the B operand
+// (chunk 1); the rest of the 16 KB is not used.  The join kernel copies the 4 KB + 4 KB of a tile's two panels
+// to the LDS once per tile; the constant chunks 2 and 3 it builds itself from C, which is left in the status block.
 // The kernel also clears what the join kernel expects to find zero (the join kernel of the call before has
 // finished by now): the XCD alignment counters, the call's result counter `counter` and, in count mode,
 // the per-point counts `counts` (n entries; may be null).
@@ -223,7 +237,11 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
   }
   const _Float16 c = (_Float16)ldexpf(1.f, m > 15 ? 15 : m);
   auto bits = [](_Float16 x) { return (uint32_t)__builtin_bit_cast(uint16_t, x); };
-  if (i == 0) status_and_max[0] = st;
+  if (i == 0) {
+    status_and_max[0] = st;
+    status_and_max[2] = bits(c) | (bits(c) << 16);
+    status_and_max[3] = bits(c);
+  }
   if (i >= npad) return;
   // the pieces of point x as two 32-bit words { p1 | p2 << 16, p3 }
   auto pieces = [&](int64_t x) -> uint2 {
@@ -240,16 +258,13 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
   const uint2 own = pieces(i);
   H[i] = make_uint4(own.x, own.y, cc.x, cc.y);
   if (Xp) {
-    const int sw = swz((int)(i & 255));
     const int r = (int)(i & 31);
     const int64_t b = i - r;
     const int64_t xa = b + aug_row_point(r), xb = b + aug_col_point(r);
     const uint2 a0 = pieces(xa), a1 = pieces(xa + 4), b0 = pieces(xb), b1 = pieces(xb + 16);
-    uint4* row = Xp + packed_index(i * 4, aug_kb, blocks);
-    row[0 ^ sw] = make_uint4(a0.x, a0.y, a1.x, a1.y);
-    row[1 ^ sw] = make_uint4(b0.x, b0.y, b1.x, b1.y);
-    row[2 ^ sw] = make_uint4(cc.x, cc.y, 0u, 0u);
-    row[3 ^ sw] = make_uint4(0u, 0u, cc.x, cc.y);
+    uint4* blk = Xp + packed_index((i >> 8) << 10, aug_kb, blocks);  // the panel's augmentation block
+    blk[i & 255] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+    blk[TILE + (i & 255)] = make_uint4(b0.x, b0.y, b1.x, b1.y);
   }
 }
 
@@ -467,9 +482,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int r16 = lane & 15, g = lane >> 4;
-  const int nsl = a.nslices;       // data slices per tile
-  const int nslT = nsl + 1;        // plus the augmentation slice (nslT >= DIST: nsl >= 2 because d is padded to 64)
+  const int nsl = a.nslices;       // slices per tile (nsl >= DIST: the host pads a short d with zero k-blocks)
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+  // the constant chunks of the augmentation step (made visible by the barrier of the prologue)
+  if (tid < 8) {
+    const uint32_t c0 = a.status[2], c1 = a.status[3];
+    *reinterpret_cast<uint4*>(lds + AUGC_OFF + (tid >> 1) * AUG_REGION_STEP + (tid & 1) * 16) =
+        (tid & 1) ? make_uint4(0u, 0u, c0, c1) : make_uint4(c0, c1, 0u, 0u);
+  }
 
   // --- global->LDS copies.  One global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 B) = 16 rows of a
   // panel; in the packed layout that is 1 KB of contiguous global memory.  Only waves 4..7 copy: wave
@@ -481,7 +501,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const char* XbA = reinterpret_cast<const char*>(a.XpA);
   const char* XbB = reinterpret_cast<const char*>(a.XpB);
   // a panel's k-blocks (16 KB each) follow each other in memory: the data blocks, then the augmentation block
-  const int64_t panel_stride = (int64_t)nslT * PANEL_BYTES;
+  const int64_t panel_stride = (int64_t)(nsl + 1) * PANEL_BYTES;
   const int cw = wave & 3;
   const bool copier = wave >= 4;
   const uint32_t voff0 = lane * 16 + cw * 1024;
@@ -496,6 +516,16 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     copy16_to_lds<PANEL_BYTES + 12288>(lds_stage, pb, voff0 + 12288);
   };
   constexpr int NCOPY = 8;  // copy instructions per slice and copying wave
+  // The operands of a tile's augmentation step: 4 KB of panel I's augmentation block and 4 KB of panel J's, one
+  // copy instruction each per copying wave, into a buffer of their own.  Issued in the tile's first slice (every
+  // wave has then left the tile before and its reads of the buffer behind), read in its last.
+  constexpr int NAUG = 2;
+  auto issue_aug = [&](uint32_t I, uint32_t J) {
+    const char* ga = XbA + (int64_t)EJ_PANEL_A(I) * panel_stride + (int64_t)nsl * PANEL_BYTES;
+    const char* gb = XbB + (int64_t)EJ_PANEL_B(J) * panel_stride + (int64_t)nsl * PANEL_BYTES;
+    copy16_to_lds<AUG_OFF>(lds0 + cw * 1024, ga, voff0);
+    copy16_to_lds<AUG_OFF + AUG_PART_BYTES>(lds0 + cw * 1024, gb, voff0 + AUG_PART_BYTES);
+  };
 
   // --- fragment read addressing (byte offsets inside a stage).  Operands of v_mfma_f32_16x16x32_f16:
   // lane l supplies point l%16 of the fragment, coordinates 8*(l/16) .. +7 of the 32-wide step; in the
@@ -513,17 +543,17 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   }
   // Operands of the augmentation step (one v_mfma_f32_32x32x16_f16 per 32 x 32 region, see there): lane l
   // supplies row (or column) m = l%32 of the region, k = 8*(l/32) .. +7, and finds its 16 bytes ready made in
-  // the augmentation slice (layout: k_aux): the A operand in chunk 0 of row m (k = 0..7) or, for k = 8..15,
-  // the indicator of bit 3 of m (chunk 2 or 3 of any row); the B operand the indicator of bit 4 of m
-  // (k = 0..7) or chunk 1 of column m (k = 8..15).  Region t of a panel adds 32 rows = 2048 B.
+  // the LDS (panel_layout.h, "the augmentation step"): the A operand in the A part of the tile's augmentation
+  // buffer, row m (chunk 0, k = 0..7) or, for k = 8..15, the constant chunk chosen by bit 3 of m (chunk 2 or 3);
+  // the B operand the constant chunk chosen by bit 4 of m (k = 0..7) or column m of the B part (chunk 1,
+  // k = 8..15).  Region t adds 32 rows = AUG_REGION_STEP in either place.
   uint32_t offA_aug, offB_aug;
   {
     const int m = lane & 31, upper = lane >> 5;
     const int rowA = wm * 128 + m, rowB = wn * 64 + m;
-    const int chunkA = upper ? 2 + ((m >> 3) & 1) : 0;  // aug_chunk_a(lane)
-    const int chunkB = upper ? 1 : 2 + (m >> 4);        // aug_chunk_b(lane)
-    offA_aug = lds0 + rowA * 64 + ((chunkA ^ swz(rowA)) << 4);
-    offB_aug = lds0 + PANEL_BYTES + rowB * 64 + ((chunkB ^ swz(rowB)) << 4);
+    const int chunkA = aug_chunk_a(lane), chunkB = aug_chunk_b(lane);
+    offA_aug = lds0 + (upper ? AUGC_OFF + 16 * (chunkA - 2) : AUG_OFF + rowA * 16);
+    offB_aug = lds0 + (upper ? AUG_OFF + AUG_PART_BYTES + rowB * 16 : AUGC_OFF + 16 * (chunkB - 2));
   }
   typedef const __attribute__((address_space(3))) char* lds_cptr;
   typedef const __attribute__((address_space(3))) half8* lds_h8ptr;
@@ -532,7 +562,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     return *reinterpret_cast<lds_h8ptr>((lds_cptr)(uintptr_t)(off[t & 1] + stage_off) + (t >> 1) * 2048);
   };
   // augmentation operand of region t (points 32 t .. 32 t + 31); addr: offA_aug or offB_aug + stage offset
-  auto aug_operand = [&](uint32_t addr, int t) -> half8 { return *reinterpret_cast<lds_h8ptr>((lds_cptr)(uintptr_t)addr + t * 2048); };
+  auto aug_operand = [&](uint32_t addr, int t) -> half8 { return *reinterpret_cast<lds_h8ptr>((lds_cptr)(uintptr_t)addr + t * AUG_REGION_STEP); };
 
   // acc[mt][nt]: the 16 x 16 block at rows 16 mt, columns 16 nt of the wave tile
   float4v acc[8][4];
@@ -605,7 +635,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   uint32_t epoch = 0, tiles_since_sync = 0;
   if (a.sync_mode >= 1) xcd_align(a.xcd_bar + tc.xcd, tc.wpx * ++epoch);
   uint32_t G = 0;  // slices computed so far (stage = G % NSTAGE); slices issued so far = G + DIST
-  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` (0 .. nslT-1) of the
+  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` (0 .. nsl-1) of the
   // current tile or, once that is fully issued, of the next one; after the last tile it keeps
   // issuing copies of valid memory into the dump area.
   int iks = 0;
@@ -625,7 +655,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     }
     pa += PANEL_BYTES;
     pb += PANEL_BYTES;
-    if (++iks == nslT) {
+    if (++iks == nsl) {
       iks = 0;
       if (issue_live && issue_on_next) {
         // The cursor has finished the tile AFTER the one being computed.  That happens only when a tile
@@ -706,9 +736,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       read_then_mfma(I2_{});
       read_then_mfma(I4_{});
     } else {
-      // the slice that follows is the augmentation slice: its six operands go where the fragments would
+      // the augmentation step follows: its six operands go where the fragments would
       // (faL[t]: A operand of region t, fb[0], fb[1]: B operands)
-      const uint32_t oa_n = st_nxt + offA_aug, ob_n = st_nxt + offB_aug;
+      const uint32_t oa_n = offA_aug, ob_n = offB_aug;
       faL[0] = aug_operand(oa_n, 0);
       faL[1] = aug_operand(oa_n, 1);
       mma4(first_c, I1_{}, I0_{}, faH, fb[0]);
@@ -727,19 +757,26 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       read_then_mfma(I6_{});
     }
   };
-  // One data slice.  LAST: last data slice of a tile (the fragments read ahead are those of the augmentation
-  // slice).  COPIER: the instance the copying waves run; the other waves run one without any copy code in it
+  // One slice.  LAST: last slice of a tile (what is read ahead are the operands of the augmentation step).
+  // COPIER: the instance the copying waves run; the other waves run one without any copy code in it
   // (the copy instructions are opaque to the scheduler and would break up the MFMA / LDS-read interleave for nothing).
-  auto data_slice = [&](auto first_c, auto last_c, auto copier_c) {
+  // second: the slice after a tile's first.
+  auto data_slice = [&](auto first_c, auto last_c, auto copier_c, bool second) {
+    constexpr bool FIRST = decltype(first_c)::value;
     constexpr bool COPIER = decltype(copier_c)::value;
     const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
-    // (a) this wave's copies of slice G+1 have landed once only those of slice G+2 are outstanding
+    // (a) this wave's copies of slice G+1 have landed once only those of slice G+2 are outstanding -- and, in a
+    //     tile's second slice, the augmentation copies issued in its first between those of slices G+1 and G+2
+    //     (from the third slice on they are older than everything that may be outstanding: they have landed, and
+    //     the barrier of that slice makes them visible, before the last slice reads them)
     if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
+    else if (COPIER && DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
     // (c) the copying waves refill the stage slice G-1 occupied with slice G+DIST, while the other wave of
     //     their SIMD starts on the MFMAs of the slice
+    if constexpr (COPIER && FIRST) issue_aug(I, J);
     if constexpr (COPIER) issue_one(G + DIST);
     // (d) the MFMAs of slice G, overlapped with the LDS reads of what follows
     mma_slice(first_c, last_c, st_cur, st_nxt);
@@ -747,8 +784,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   };
 
 #ifdef EJOIN_EXP_CYCLE_MARKS
-  // sections: 0 tile switch, 1 first data slice, 2 middle data slices, 3 last data slice, 4 wait + barrier of the
-  // augmentation slice, 5 its copy issue, 6 augmentation MFMAs + filter + exact path
+  // sections: 0 tile cursor, 1 first slice, 2 middle slices, 3 last slice, 4 augmentation MFMAs + filter + exact path,
+  // 5 reads of the next tile's first fragments (a mark waits for them to arrive: the section is their latency),
+  // 6 the periodic re-alignment of the XCD's workgroups, 7 the wait for all copies in flight before it
   unsigned long long mark_sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   unsigned long long mark_prev = __builtin_amdgcn_s_memtime();
 #define EJ_MARK(k)                                                  \
@@ -761,23 +799,23 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 #define EJ_MARK(k)
 #endif
   while (have) {
-    // ---------------- the nsl >= 2 data slices of the tile
+    // ---------------- the nsl >= 3 slices of the tile
     EJ_MARK(0)
     if (copier) {
-      data_slice(T_{}, F_{}, T_{});
+      data_slice(T_{}, F_{}, T_{}, false);
       EJ_MARK(1)
-      for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, T_{});
+      for (int ks = 1; ks < nsl - 1; ++ks) data_slice(F_{}, F_{}, T_{}, ks == 1);
       EJ_MARK(2)
-      data_slice(F_{}, T_{}, T_{});
+      data_slice(F_{}, T_{}, T_{}, false);
     } else {
-      data_slice(T_{}, F_{}, F_{});
+      data_slice(T_{}, F_{}, F_{}, false);
       EJ_MARK(1)
-      for (int ks = 2; ks < nsl; ++ks) data_slice(F_{}, F_{}, F_{});
+      for (int ks = 1; ks < nsl - 1; ++ks) data_slice(F_{}, F_{}, F_{}, false);
       EJ_MARK(2)
-      data_slice(F_{}, T_{}, F_{});
+      data_slice(F_{}, T_{}, F_{}, false);
     }
     EJ_MARK(3)
-    // ---------------- the augmentation slice: one step, then the filter.
+    // ---------------- the augmentation step, then the filter.
     // The step adds -s_i/2 - s_j/2 to every accumulator with eight v_mfma_f32_32x32x16_f16, one per 32 x 32
     // region of the wave tile, half the matrix-core time that 32 more 16x16x32 (with 26 of 32 products zero)
     // would take.  A region's accumulator is its four 16 x 16 blocks' registers side by side, R = (mt2, nt2):
@@ -790,13 +828,6 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     // and each is exact, as in a plain { P, c } . { c, P } step.
     float16v R[4][2];
     {
-      if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
-      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
-      wg_barrier();
-      EJ_MARK(4)
-      issue_one(G + DIST);
-      EJ_MARK(5)
-      ++G;
 #pragma unroll
       for (int mt2 = 0; mt2 < 4; ++mt2)
 #pragma unroll
@@ -926,18 +957,22 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       if (diag) exact_path(T_{});
       else exact_path(F_{});
     }
-    EJ_MARK(6)
-    // first fragments of the next tile (slice G was certified by the augmentation slice's barrier);
+    EJ_MARK(4)
+    // first fragments of the next tile (slice G was certified by the barrier of the tile's last slice);
     // read after the filter to keep its registers free
     load_first((G % NSTAGE) * STAGE_BYTES);
+    EJ_MARK(5)
     I = In;
     J = Jn;
     have = have_next;
     if (have) {
       if (a.sync_mode >= 1 && ++tiles_since_sync >= (uint32_t)a.sync_mode) {
         tiles_since_sync = 0;
+        EJ_MARK(0)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        EJ_MARK(7)
         xcd_align(a.xcd_bar + tc.xcd, tc.wpx * ++epoch);
+        EJ_MARK(6)
       }
       have_next = tc.next(In, Jn);
       issue_on_next = false;  // the issue cursor, if it had moved on, is now on the current tile
@@ -1041,6 +1076,9 @@ int fail_hip(ejoin_ctx* ctx, hipError_t e, const char* what) {
 int64_t pad_rows(int64_t n) { return (n + TILE - 1) / TILE * TILE; }
 int64_t pad_dims(int32_t d) { return ((int64_t)d + KPAD - 1) / KPAD * KPAD; }
 int k_blocks(int32_t d) { return (int)(pad_dims(d) / KSLICE); }  // 32-coordinate k-blocks = MFMA steps per inner product
+// Slices per tile of the join kernel for `data_blocks` k-blocks of data: its copy pipeline runs DIST slices ahead and
+// looks one tile ahead, so a tile has at least DIST slices; a packed copy with fewer data blocks gets zero blocks.
+int ring_blocks(int data_blocks) { return data_blocks < DIST ? DIST : data_blocks; }
 
 int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int64_t ld) {
   if (!ctx || !X) return EJOIN_EINVAL;
@@ -1053,8 +1091,9 @@ int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int6
 
 bool bad_eps(float eps) { return !(eps >= 0.f) || !isfinite(eps); }
 
-// Bytes of packed copy for `rows` (padded) points of d coordinates: the data k-blocks plus the augmentation block.
-int64_t packed_bytes(int64_t rows, int64_t dpad) { return rows * (dpad + KSLICE) * 2; }
+// Bytes of packed copy for `rows` (padded) points of dpad coordinates: the data k-blocks (zero blocks included) plus
+// the augmentation block.
+int64_t packed_bytes(int64_t rows, int64_t dpad) { return rows * (int64_t)(ring_blocks((int)(dpad / KSLICE)) + 1) * KSLICE * 2; }
 
 // The context's own workspace for `rows` points in total (each set padded to a multiple of TILE).
 // dpad = 0: only the per-point arrays (norms, augmentation rows); dpad > 0: also the packed copies.
@@ -1120,7 +1159,7 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
   const int64_t npad = pad_rows(n);
   const int64_t waves = ((Xp ? npad : n) + 15) / 16;
   const dim3 grid((unsigned)((waves + 3) / 4));
-  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, k_blocks(d) + 1);
+  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, ring_blocks(k_blocks(d)) + 1);
   else hipLaunchKernelGGL(k_norms<false>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, 0);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
@@ -1128,7 +1167,8 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
 
 // Augmentation rows of one set from its norms and the running maximum of all norms.
 // Xp: the set's packed copy, whose panels get their augmentation k-block (k-block number `data_blocks`, behind the
-// data blocks; null for the dense-tile call); counter / counts: what the kernel clears on the way (may be null).
+// data blocks, zero blocks included; null for the dense-tile call); counter / counts: what the kernel clears on the
+// way (may be null).
 int launch_aux(ejoin_ctx* ctx, uint32_t* status, const float* s, int64_t n, uint4* H, uint4* Xp, int data_blocks,
                unsigned long long* counter, uint32_t* counts, hipStream_t st) {
   const int64_t npad = pad_rows(n);
@@ -1242,7 +1282,7 @@ int run_join(ejoin_ctx* ctx, const Workspace& w, bool own, const uint16_t* XA, i
              int64_t ldB, int32_t d, float eps, const Results& r, hipStream_t st, const uint32_t* batch_rows = nullptr, int nbatches = 0) {
   const bool self = (XB == nullptr);
   const int64_t padA = pad_rows(nA), padB = self ? 0 : pad_rows(nB);
-  const int nkb = k_blocks(d);
+  const int nkb = ring_blocks(k_blocks(d));
   float* sA = w.s;
   float* sB = w.s + padA;
   uint4* HA = w.H;
@@ -1301,7 +1341,7 @@ int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, in
   const int64_t padQ = pad_rows(nQ);
   EJ_RC(ensure_workspace(ctx, padQ, pad_dims(d)));
   const Workspace& w = ctx->ws;
-  const int nkb = k_blocks(d);
+  const int nkb = ring_blocks(k_blocks(d));
   EJ_RC(begin_call(ctx, w, true, st));
   EJ_RC(launch_norms(ctx, XQ, nQ, d, ldQ, w.s, w.status + 1, w.Xp, st));
   hipLaunchKernelGGL(k_merge_max, dim3(1), dim3(64), 0, st, w.status + 1, P->max_bits);
