@@ -591,7 +591,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   uint32_t* stg = reinterpret_cast<uint32_t*>(lds + STG_OFF + wave * STG_WAVE_BYTES);
   uint32_t fill = 0;               // wave-uniform
   unsigned long long hits = 0;     // count mode: pairs found by this wave
-  bool dirty = false;              // stores/atomics issued since the last vmcnt(0): counted waits are unsafe
+  bool dirty = false;              // stores/atomics issued by the rare path of the current tile (see there)
   auto flush = [&]() {
     if (fill == 0) return;
     unsigned long long base = 0;
@@ -632,7 +632,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     return;
   }
   bool have_next = tc.next(In, Jn);
-  uint32_t epoch = 0, tiles_since_sync = 0;
+  uint32_t epoch = 0;
+  // tiles until the next re-alignment of the XCD's workgroups (never: a count no workgroup reaches)
+  uint32_t sync_left = a.sync_mode >= 1 ? (uint32_t)a.sync_mode : 0xFFFFFFFFu;
   if (a.sync_mode >= 1) xcd_align(a.xcd_bar + tc.xcd, tc.wpx * ++epoch);
   uint32_t G = 0;  // slices computed so far (stage = G % NSTAGE); slices issued so far = G + DIST
   // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` (0 .. nsl-1) of the
@@ -769,8 +771,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     //     tile's second slice, the augmentation copies issued in its first between those of slices G+1 and G+2
     //     (from the third slice on they are older than everything that may be outstanding: they have landed, and
     //     the barrier of that slice makes them visible, before the last slice reads them)
-    if (dirty) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); dirty = false; }
-    else if (COPIER && DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
+    if (COPIER && DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
@@ -954,8 +955,16 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
           }
         }
       };
-      if (diag) exact_path(T_{});
-      else exact_path(F_{});
+      if (blocks_hit) {
+        if (diag) exact_path(T_{});
+        else exact_path(F_{});
+        // The stores and atomics of the path count on vmcnt like the copies, but complete in any order: the counted
+        // waits of the slices hold only once they are all done.
+        if (dirty) {
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          dirty = false;
+        }
+      }
     }
     EJ_MARK(4)
     // first fragments of the next tile (slice G was certified by the barrier of the tile's last slice);
@@ -966,8 +975,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     J = Jn;
     have = have_next;
     if (have) {
-      if (a.sync_mode >= 1 && ++tiles_since_sync >= (uint32_t)a.sync_mode) {
-        tiles_since_sync = 0;
+      if (--sync_left == 0) {
+        sync_left = (uint32_t)a.sync_mode;
         EJ_MARK(0)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         EJ_MARK(7)

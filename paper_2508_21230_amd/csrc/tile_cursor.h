@@ -40,15 +40,16 @@ struct TileCursor {
   uint32_t self, nsbA, nsbB, ntA, ntB;
   uint32_t rem;          // position of this workgroup's next tile, counted from the first tile of the current rectangle
   uint32_t P, Q, sbi;    // current super-block: coordinates and linear index
-  uint32_t fast_left;    // complete super-blocks that follow the current one in its row (see next)
-  uint32_t start, stride;  // (row-major ablation only) first tile and stride of this workgroup
+  uint32_t fast_left;    // steps of the common kind that may follow (see next) ...
+  uint32_t fast_row, fast_col;  // ... and what they need: the tile's place in its rectangle, row already in tiles of the grid
+#ifdef EJOIN_ABL_ROWMAJOR_TILES
+  uint32_t start, stride;  // first tile and stride of this workgroup
+#endif
   // self_join: upper triangle of an nt x nt grid (nt_a == nt_b); otherwise the whole nt_a x nt_b grid.
   // sb_row_begin .. sb_row_end - 1: the rows of super-blocks this launch covers (a join may be cut into several
   // launches by rows of super-blocks; 0 .. UINT32_MAX = everything)
   EJ_HD void init(uint32_t block, uint32_t nblocks, uint32_t self_join, uint32_t nt_a, uint32_t nt_b, uint32_t sb_row_begin = 0,
                   uint32_t sb_row_end = 0xFFFFFFFFu) {
-    start = block;
-    stride = 0;
     xcd = block % EJ_NUM_XCD;
     wpx = (nblocks - xcd + EJ_NUM_XCD - 1) / EJ_NUM_XCD;  // workgroups with this XCD id
     self = self_join;
@@ -62,7 +63,9 @@ struct TileCursor {
     Q = self_join ? sb_row_begin : 0;
     sbi = 0;
     fast_left = 0;
+    fast_row = fast_col = 0;
 #ifdef EJOIN_ABL_ROWMAJOR_TILES
+    start = block;
     stride = nblocks;
 #endif
   }
@@ -97,22 +100,21 @@ struct TileCursor {
     // The common step first.  All eight wavefronts of a workgroup run this code at the same time, between two
     // tiles, with nothing else to overlap it: every instruction here is paid eight times on the one scalar unit.
     // Along a row of super-blocks nearly every rectangle is a complete 8 x 4 one; the last tile came from such
-    // a rectangle (fast_left counts the complete super-blocks that follow it in the row) and the next one is
-    // 32 entries further on, at the same place (rem / 4, rem % 4) of the next rectangle, whose offsets inside
-    // its super-block rotate with the super-block index.
+    // a rectangle and the next one sits in the next rectangle, at place (fast_row, fast_col) of it, whose offsets
+    // inside its super-block rotate with the super-block index.  With 32 workgroups per XCD (the whole chip) that
+    // place is the same from rectangle to rectangle and the steps of this kind go on to the end of the row; with
+    // another number the general code below is asked again after each one.  (fast_left: how many may follow.)
 #ifndef EJOIN_CURSOR_NO_FAST_PATH
-    if (fast_left != 0 && rem - 32u < 32u) {
+    if (fast_left != 0) {
       --fast_left;
-      rem -= 32u;
       ++Q;
       ++sbi;
-      const uint32_t xp = (xcd + sbi) & 7;
-      I = EJ_UNIFORM(P * EJ_SB + (xp >> 2) * 8 + (rem >> 2));
-      J = EJ_UNIFORM(Q * EJ_SB + (xp & 3) * 4 + (rem & 3));
-      rem += wpx;
+      const uint32_t t = xcd + sbi;  // rectangle number (t % 8): row offset 8 (t / 4 % 2), column offset 4 (t % 4)
+      I = EJ_UNIFORM(fast_row + ((t << 1) & 8u));
+      J = EJ_UNIFORM(Q * EJ_SB + fast_col + ((t << 2) & 12u));
+      rem = rem - 32u + wpx;
       return true;
     }
-    fast_left = 0;
 #endif
     while (P < nsbA) {
       const uint32_t xp = (xcd + sbi) & 7;
@@ -160,10 +162,16 @@ struct TileCursor {
         // and off the diagonal (Q' > P; the self-join starts each row on the diagonal, so Q >= P here).
         // A rectangle of 32 tiles maps position p to (p / 4, p % 4) whatever kind it is, so the fast step
         // may follow any rectangle; it only requires the ones it enters to be complete.
+        // The next tile is entry rem - 32 of the next rectangle, if that is one of its 32.
         {
           const uint32_t qf = ntB / EJ_SB;
           const bool rows_ok = self ? true : (P < ntA / EJ_SB);
-          fast_left = (v == 32u && rows_ok && Q + 1 < qf) ? qf - 1 - Q : 0u;
+          const uint32_t pos = rem - 32u;
+          uint32_t steps = (v == 32u && rows_ok && Q + 1 < qf && pos < 32u) ? qf - 1 - Q : 0u;
+          if (wpx != 32u && steps > 1u) steps = 1u;
+          fast_left = steps;
+          fast_row = P * EJ_SB + (pos >> 2);
+          fast_col = pos & 3u;
         }
 #endif
         return true;
