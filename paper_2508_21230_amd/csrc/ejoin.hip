@@ -1262,7 +1262,7 @@ int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, 
     // re-align the workgroups of each XCD every few hundred microseconds: about 512 slices
     // (measured on MI355X: +12..16 % over never aligning; every tile costs more than it gains)
     const int per = 512 / (a.nslices + 1);
-    a.sync_mode = per < 8 ? 8 : (per > 64 ? 64 : per);
+    a.sync_mode = per < 8 ? 8 : (per > 128 ? 128 : per);
 #ifdef EJOIN_ABL_NOALIGN
     a.sync_mode = 0;
 #endif
