@@ -55,7 +55,7 @@ typedef struct ejoin_ctx ejoin_ctx;
 
 /* Create a context on HIP device `device`.  The context owns a few hundred bytes of device
  * status words and a workspace: 20 bytes per point (the norms s_i and their FP16 split) plus, for
- * the join calls, a re-laid-out copy of X (roundup(n,256) * (max(roundup(d,64), 96) + 32) * 2 bytes).  The workspace
+ * the join calls, a re-laid-out copy of X (roundup(n,256) * (roundup(d,64) + 32) * 2 bytes).  The workspace
  * is grown on demand with hipMalloc, or ahead of time by ejoin_reserve.  A call that has to grow the
  * workspace frees the old one first, which waits for the device to be idle: only calls that find the
  * workspace large enough "enqueue and return".  Host pointer out. */
@@ -129,7 +129,7 @@ int ejoin_selfjoin_pairs_to_host(ejoin_ctx* ctx, const uint16_t* X, int64_t n, i
  * the library runs on holds it from load to process end) instead of the context's workspace.  The call
  * allocates and frees nothing, whatever its arguments.  Arguments, results and conventions are those
  * of ejoin_selfjoin_pairs, and so are the results, bit for bit.  The problem must fit:
- *     256 + roundup(20 * npad, 512) + npad * (max(roundup(d,64), 96) + 32) * 2  <=  EJOIN_STATIC_SCRATCH_BYTES,
+ *     256 + roundup(20 * npad, 512) + npad * (roundup(d,64) + 32) * 2  <=  EJOIN_STATIC_SCRATCH_BYTES,
  * npad = roundup(n,256) (n = 100,000 at d = 128 does; so does n = 20,000 at d = 960); otherwise
  * EJOIN_ESCRATCH is returned and nothing is enqueued.  All contexts of a GPU share the one array, which
  * keeps the last call's contents (the call clears what it needs zero): calls of this entry point that

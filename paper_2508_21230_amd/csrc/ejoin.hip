@@ -85,7 +85,7 @@ struct JoinArgs {
   int64_t nA, nB;
   int self;                // 1: self-join (upper triangle, self pairs), 0: two different sets (full rectangle)
   uint32_t* status;        // status block of the workspace (see k_reset)
-  int nslices;  // k-blocks of data per panel = slices per tile, at least DIST (the augmentation block follows them)
+  int nslices;  // roundup(d, 64) / 32 : k-blocks of data per panel = slices per tile (the augmentation block follows them)
   float thr;    // pass <=> acc' >= thr, thr = -eps^2 / 2
   uint32_t ntilesA, ntilesB;  // ceil(n / TILE)
   uint32_t sb_row_begin, sb_row_end;  // rows of super-blocks this launch covers (a join returned in batches is cut by them)
@@ -146,8 +146,7 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 template <bool PACK>
 __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, int64_t n, int64_t npad, int64_t ld, int k32steps,
                                                float* __restrict__ s, uint32_t* __restrict__ max_bits, uint4* __restrict__ Xp,
-                                               int blocks /* k-blocks per panel of Xp: the k32steps data blocks, zero blocks
-                                                              up to the join kernel's minimum, the augmentation block */) {
+                                               int blocks /* k-blocks per panel of Xp: k32steps + 1 */) {
   const int lane = threadIdx.x & 63;
   const int64_t blk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t row0 = blk * 16;
@@ -156,7 +155,7 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
   int64_t at = 0;
   if (PACK) at = place_of(row_own, lane >> 4);
   if (PACK && row0 >= n) {  // padding rows only
-    for (int k = 0; k < blocks - 1; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
+    for (int k = 0; k < k32steps; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
     return;
   }
   const bool valid = row_own < n;
@@ -168,8 +167,6 @@ __global__ __launch_bounds__(256) void k_norms(const uint16_t* __restrict__ X, i
     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, a, acc, 0, 0, 0);
     if (PACK) Xp[packed_index(at, k, blocks)] = valid ? __builtin_bit_cast(uint4, a) : make_uint4(0, 0, 0, 0);
   }
-  if (PACK)
-    for (int k = k32steps; k < blocks - 1; ++k) Xp[packed_index(at, k, blocks)] = make_uint4(0, 0, 0, 0);
   // element (row, col) of the 16 x 16 block sits in lane col + 16 * (row / 4), register row % 4
   const int c = lane & 15, g = lane >> 4;
   uint32_t bits = 0;
@@ -482,7 +479,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int r16 = lane & 15, g = lane >> 4;
-  const int nsl = a.nslices;       // slices per tile (nsl >= DIST: the host pads a short d with zero k-blocks)
+  const int nsl = a.nslices;       // slices per tile (nsl >= 2: d is padded to 64)
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
   // the constant chunks of the augmentation step (made visible by the barrier of the prologue)
   if (tid < 8) {
@@ -505,7 +502,16 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   const int cw = wave & 3;
   const bool copier = wave >= 4;
   const uint32_t voff0 = lane * 16 + cw * 1024;
-  auto issue_slice = [&](const char* pa, const char* pb, uint32_t lds_stage /* LDS address of the stage + cw*1024 */) {
+  // (a copy takes its base address in scalar registers; the addresses are uniform, which is said explicitly because the
+  // compiler, when it keeps such a pointer in vector registers, does not always move it back by itself)
+  auto uniform_ptr = [](const char* p) -> const char* {
+    const uint64_t b = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+  };
+  auto issue_slice = [&](const char* pa_, const char* pb_, uint32_t lds_stage /* LDS address of the stage + cw*1024 */) {
+    const char* pa = uniform_ptr(pa_);
+    const char* pb = uniform_ptr(pb_);
     copy16_to_lds<0>(lds_stage, pa, voff0);
     copy16_to_lds<4096>(lds_stage, pa, voff0 + 4096);
     copy16_to_lds<8192>(lds_stage, pa, voff0 + 8192);
@@ -521,8 +527,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // wave has then left the tile before and its reads of the buffer behind), read in its last.
   constexpr int NAUG = 2;
   auto issue_aug = [&](uint32_t I, uint32_t J) {
-    const char* ga = XbA + (int64_t)EJ_PANEL_A(I) * panel_stride + (int64_t)nsl * PANEL_BYTES;
-    const char* gb = XbB + (int64_t)EJ_PANEL_B(J) * panel_stride + (int64_t)nsl * PANEL_BYTES;
+    const char* ga = uniform_ptr(XbA + (int64_t)EJ_PANEL_A(I) * panel_stride + (int64_t)nsl * PANEL_BYTES);
+    const char* gb = uniform_ptr(XbB + (int64_t)EJ_PANEL_B(J) * panel_stride + (int64_t)nsl * PANEL_BYTES);
     copy16_to_lds<AUG_OFF>(lds0 + cw * 1024, ga, voff0);
     copy16_to_lds<AUG_OFF + AUG_PART_BYTES>(lds0 + cw * 1024, gb, voff0 + AUG_PART_BYTES);
   };
@@ -621,7 +627,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // ---------------- prologue
   TileCursor tc;
   tc.init(blockIdx.x, gridDim.x, (uint32_t)a.self, a.ntilesA, a.ntilesB, a.sb_row_begin, a.sb_row_end);
-  uint32_t I = 0, J = 0, In = 0, Jn = 0;
+  // the tile being computed and the two after it (the copies run up to two tiles ahead, see issue_one)
+  uint32_t I = 0, J = 0, In = 0, Jn = 0, In2 = 0, Jn2 = 0;
   bool have = tc.next(I, J);
   // a workgroup that leaves (now, or after its last tile) releases every later alignment of its XCD
   auto xcd_leave = [&]() {
@@ -632,18 +639,19 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     return;
   }
   bool have_next = tc.next(In, Jn);
+  bool have_next2 = have_next && tc.next(In2, Jn2);
   uint32_t epoch = 0;
   // tiles until the next re-alignment of the XCD's workgroups (never: a count no workgroup reaches)
   uint32_t sync_left = a.sync_mode >= 1 ? (uint32_t)a.sync_mode : 0xFFFFFFFFu;
   if (a.sync_mode >= 1) xcd_align(a.xcd_bar + tc.xcd, tc.wpx * ++epoch);
   uint32_t G = 0;  // slices computed so far (stage = G % NSTAGE); slices issued so far = G + DIST
-  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` (0 .. nsl-1) of the
-  // current tile or, once that is fully issued, of the next one; after the last tile it keeps
-  // issuing copies of valid memory into the dump area.
+  // The issue cursor runs DIST slices ahead of the compute cursor: slice `iks` (0 .. nsl-1) of the tile
+  // `ahead` tiles after the one being computed.  With nsl >= 2 and DIST <= 3 that is at most two tiles ahead
+  // (two when a tile has no more slices than are in flight: d <= 96).  After the last tile it keeps issuing
+  // copies of valid memory into the dump area.
   int iks = 0;
-  bool issue_live = true;       // the issue cursor still points at real work
-  bool issue_on_next = false;   // ... of the tile after the one being computed
-  bool issue_pending = false;   // ... and has finished that one too (see issue_one)
+  int ahead = 0;
+  bool issue_live = true;       // the issue cursor points at real work
   const char* pa = XbA + (int64_t)EJ_PANEL_A(I) * panel_stride;
   const char* pb = XbB + (int64_t)EJ_PANEL_B(J) * panel_stride;
   const uint32_t lds_w = lds0 + cw * 1024;
@@ -659,19 +667,12 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     pb += PANEL_BYTES;
     if (++iks == nsl) {
       iks = 0;
-      if (issue_live && issue_on_next) {
-        // The cursor has finished the tile AFTER the one being computed.  That happens only when a tile
-        // has exactly DIST slices (d <= 64), and then with the last issue of the current tile; which
-        // tile comes two ahead is decided at the end of this tile, where the cursor is set on it.
-        issue_pending = true;
-        issue_live = false;
-      } else {
-        const bool to_next = issue_live && have_next;
-        issue_live = to_next;
-        issue_on_next = to_next;
-        pa = XbA + (int64_t)(to_next ? EJ_PANEL_A(In) : 0) * panel_stride;
-        pb = XbB + (int64_t)(to_next ? EJ_PANEL_B(Jn) : 0) * panel_stride;
-      }
+      ++ahead;
+      const bool first_after = ahead == 1;
+      issue_live = first_after ? have_next : have_next2;
+      const uint32_t ti = first_after ? In : In2, tj = first_after ? Jn : Jn2;
+      pa = XbA + (int64_t)(issue_live ? EJ_PANEL_A(ti) : 0) * panel_stride;
+      pb = XbB + (int64_t)(issue_live ? EJ_PANEL_B(tj) : 0) * panel_stride;
     }
   };
   for (int q = 0; q < DIST; ++q) issue_one(q);
@@ -800,7 +801,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 #define EJ_MARK(k)
 #endif
   while (have) {
-    // ---------------- the nsl >= 3 slices of the tile
+    // ---------------- the nsl >= 2 slices of the tile
     EJ_MARK(0)
     if (copier) {
       data_slice(T_{}, F_{}, T_{}, false);
@@ -974,6 +975,10 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     I = In;
     J = Jn;
     have = have_next;
+    In = In2;
+    Jn = Jn2;
+    have_next = have_next2;
+    --ahead;  // (at least 1 before: the issue cursor has left the tile that was just finished)
     if (have) {
       if (--sync_left == 0) {
         sync_left = (uint32_t)a.sync_mode;
@@ -983,15 +988,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
         xcd_align(a.xcd_bar + tc.xcd, tc.wpx * ++epoch);
         EJ_MARK(6)
       }
-      have_next = tc.next(In, Jn);
-      issue_on_next = false;  // the issue cursor, if it had moved on, is now on the current tile
-      if (issue_pending) {    // ... or already past it: put it on the tile just chosen
-        issue_pending = false;
-        issue_live = have_next;
-        issue_on_next = have_next;
-        pa = XbA + (int64_t)(have_next ? EJ_PANEL_A(In) : 0) * panel_stride;
-        pb = XbB + (int64_t)(have_next ? EJ_PANEL_B(Jn) : 0) * panel_stride;
-      }
+      have_next2 = have_next && tc.next(In2, Jn2);
     }
   }
 #ifdef EJOIN_EXP_CYCLE_MARKS
@@ -1085,9 +1082,6 @@ int fail_hip(ejoin_ctx* ctx, hipError_t e, const char* what) {
 int64_t pad_rows(int64_t n) { return (n + TILE - 1) / TILE * TILE; }
 int64_t pad_dims(int32_t d) { return ((int64_t)d + KPAD - 1) / KPAD * KPAD; }
 int k_blocks(int32_t d) { return (int)(pad_dims(d) / KSLICE); }  // 32-coordinate k-blocks = MFMA steps per inner product
-// Slices per tile of the join kernel for `data_blocks` k-blocks of data: its copy pipeline runs DIST slices ahead and
-// looks one tile ahead, so a tile has at least DIST slices; a packed copy with fewer data blocks gets zero blocks.
-int ring_blocks(int data_blocks) { return data_blocks < DIST ? DIST : data_blocks; }
 
 int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int64_t ld) {
   if (!ctx || !X) return EJOIN_EINVAL;
@@ -1100,9 +1094,8 @@ int check_common(const ejoin_ctx* ctx, const void* X, int64_t n, int32_t d, int6
 
 bool bad_eps(float eps) { return !(eps >= 0.f) || !isfinite(eps); }
 
-// Bytes of packed copy for `rows` (padded) points of dpad coordinates: the data k-blocks (zero blocks included) plus
-// the augmentation block.
-int64_t packed_bytes(int64_t rows, int64_t dpad) { return rows * (int64_t)(ring_blocks((int)(dpad / KSLICE)) + 1) * KSLICE * 2; }
+// Bytes of packed copy for `rows` (padded) points of dpad coordinates: the data k-blocks plus the augmentation block.
+int64_t packed_bytes(int64_t rows, int64_t dpad) { return rows * (dpad + KSLICE) * 2; }
 
 // The context's own workspace for `rows` points in total (each set padded to a multiple of TILE).
 // dpad = 0: only the per-point arrays (norms, augmentation rows); dpad > 0: also the packed copies.
@@ -1168,7 +1161,7 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
   const int64_t npad = pad_rows(n);
   const int64_t waves = ((Xp ? npad : n) + 15) / 16;
   const dim3 grid((unsigned)((waves + 3) / 4));
-  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, ring_blocks(k_blocks(d)) + 1);
+  if (Xp) hipLaunchKernelGGL(k_norms<true>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, k_blocks(d) + 1);
   else hipLaunchKernelGGL(k_norms<false>, grid, dim3(256), 0, st, X, n, npad, ld, k_blocks(d), s, max_bits, Xp, 0);
   EJ_TRY(hipGetLastError());
   return EJOIN_OK;
@@ -1176,8 +1169,7 @@ int launch_norms(ejoin_ctx* ctx, const uint16_t* X, int64_t n, int32_t d, int64_
 
 // Augmentation rows of one set from its norms and the running maximum of all norms.
 // Xp: the set's packed copy, whose panels get their augmentation k-block (k-block number `data_blocks`, behind the
-// data blocks, zero blocks included; null for the dense-tile call); counter / counts: what the kernel clears on the
-// way (may be null).
+// data blocks; null for the dense-tile call); counter / counts: what the kernel clears on the way (may be null).
 int launch_aux(ejoin_ctx* ctx, uint32_t* status, const float* s, int64_t n, uint4* H, uint4* Xp, int data_blocks,
                unsigned long long* counter, uint32_t* counts, hipStream_t st) {
   const int64_t npad = pad_rows(n);
@@ -1291,7 +1283,7 @@ int run_join(ejoin_ctx* ctx, const Workspace& w, bool own, const uint16_t* XA, i
              int64_t ldB, int32_t d, float eps, const Results& r, hipStream_t st, const uint32_t* batch_rows = nullptr, int nbatches = 0) {
   const bool self = (XB == nullptr);
   const int64_t padA = pad_rows(nA), padB = self ? 0 : pad_rows(nB);
-  const int nkb = ring_blocks(k_blocks(d));
+  const int nkb = k_blocks(d);
   float* sA = w.s;
   float* sB = w.s + padA;
   uint4* HA = w.H;
@@ -1350,7 +1342,7 @@ int run_join_prepared(ejoin_ctx* ctx, const ejoin_set* P, const uint16_t* XQ, in
   const int64_t padQ = pad_rows(nQ);
   EJ_RC(ensure_workspace(ctx, padQ, pad_dims(d)));
   const Workspace& w = ctx->ws;
-  const int nkb = ring_blocks(k_blocks(d));
+  const int nkb = k_blocks(d);
   EJ_RC(begin_call(ctx, w, true, st));
   EJ_RC(launch_norms(ctx, XQ, nQ, d, ldQ, w.s, w.status + 1, w.Xp, st));
   hipLaunchKernelGGL(k_merge_max, dim3(1), dim3(64), 0, st, w.status + 1, P->max_bits);

@@ -149,9 +149,9 @@ def test_edge_sizes(ej, n, d):
 
 @pytest.mark.parametrize("n,d", [(6500, 64), (7000, 40), (6200, 128), (5900, 192)])
 def test_more_tiles_than_workgroups_at_small_d(ej, n, d):
-    """Every workgroup walks several tiles (351 .. 406 tiles on 256 workgroups).  At d <= 64 a tile has as many
-    slices as the copy pipeline runs ahead, so the copy cursor finishes the tile after the current one before the
-    tile after that is known."""
+    """Every workgroup walks several tiles (351 .. 406 tiles on 256 workgroups).  At d <= 64 a tile has two slices and
+    the copy pipeline runs three ahead: the copy cursor works on the tile after the next one while the current one is
+    still being computed."""
     print(f"multi-tile n={n} d={d}", flush=True)
     rng = np.random.default_rng(n + d)
     X = rng.random((n, d), dtype=np.float32).astype(np.float16).view(np.uint16)
