@@ -59,15 +59,14 @@ constexpr int SB = (int)EJ_SB;
 constexpr int PANEL_BYTES = TILE * KSLICE * 2;  // 16 KB : one operand panel of one stage
 constexpr int STAGE_BYTES = 2 * PANEL_BYTES;    // A panel + B panel
 constexpr int DUMP_OFF = NSTAGE * STAGE_BYTES;  // 1 KB that absorbs the copies issued past the end of the work
-// Operands of the augmentation step of the tile being computed (see k_aux): 16 bytes per row of the A panel (4 KB),
-// then 16 bytes per column of the B panel (4 KB); and the two constant chunks { C, 0 } and { 0, C } of that step,
-// repeated every 512 bytes (so that "region t" is the same address step for every lane of an operand read)
+// Operands of the augmentation step of the tile being computed: 16 bytes per row of the A panel (4 KB), 16 bytes per
+// column of the B panel (4 KB), and the two constant chunks of that step (layout: panel_layout.h, "a tile's
+// augmentation buffer")
 constexpr int AUG_OFF = DUMP_OFF + 1024;
-constexpr int AUG_PART_BYTES = TILE * 16;
-constexpr int AUGC_OFF = AUG_OFF + 2 * AUG_PART_BYTES;
-constexpr int AUG_REGION_STEP = 32 * 16;        // 32 rows of 16 bytes
-constexpr int AUGC_BYTES = 4 * AUG_REGION_STEP;
-constexpr int STG_OFF = AUGC_OFF + AUGC_BYTES;  // per-wave result staging: STG_CAP entries of (i, j, d2)
+constexpr int AUG_PART_BYTES = EJ_AUG_PART;
+constexpr int AUGC_OFF = AUG_OFF + EJ_AUG_CONST;
+constexpr int AUG_REGION_STEP = EJ_AUG_REGION_STEP;
+constexpr int STG_OFF = AUG_OFF + EJ_AUG_BYTES;  // per-wave result staging: STG_CAP entries of (i, j, d2)
 constexpr int STG_CAP = 128;
 constexpr int STG_WAVE_BYTES = STG_CAP * 12;
 constexpr int LDS_BYTES = STG_OFF + 8 * STG_WAVE_BYTES;
@@ -260,8 +259,8 @@ __global__ void k_aux(const float* __restrict__ s, int64_t n, int64_t npad, uint
     const int64_t xa = b + aug_row_point(r), xb = b + aug_col_point(r);
     const uint2 a0 = pieces(xa), a1 = pieces(xa + 4), b0 = pieces(xb), b1 = pieces(xb + 16);
     uint4* blk = Xp + packed_index((i >> 8) << 10, aug_kb, blocks);  // the panel's augmentation block
-    blk[i & 255] = make_uint4(a0.x, a0.y, a1.x, a1.y);
-    blk[TILE + (i & 255)] = make_uint4(b0.x, b0.y, b1.x, b1.y);
+    blk[aug_block_unit((int)(i & 255), 0)] = make_uint4(a0.x, a0.y, a1.x, a1.y);
+    blk[aug_block_unit((int)(i & 255), 1)] = make_uint4(b0.x, b0.y, b1.x, b1.y);
   }
 }
 
@@ -405,7 +404,7 @@ __global__ __launch_bounds__(64) void k_dist2_tile(const uint16_t* __restrict__ 
     const int ra = aug_row_point(m), rb = aug_col_point(m);
     const uint4 h0 = H[row_a(ra)], h1 = H[row_a(ra + 4)];
     const uint4 q0 = H[row_b(rb)], q1 = H[row_b(rb + 16)];
-    // the four chunks of the operand rows, as k_aux writes them for the join kernel
+    // the four chunks of the operand rows (panel_layout.h, "the augmentation step"), built here from the H rows
     const uint4 chunks_a[4] = {make_uint4(h0.x, h0.y, h1.x, h1.y), make_uint4(0, 0, 0, 0), make_uint4(h0.z, h0.w, 0, 0), make_uint4(0, 0, h0.z, h0.w)};
     const uint4 chunks_b[4] = {make_uint4(0, 0, 0, 0), make_uint4(q0.x, q0.y, q1.x, q1.y), make_uint4(q0.z, q0.w, 0, 0), make_uint4(0, 0, q0.z, q0.w)};
     const int ca = aug_chunk_a(lane), cb = aug_chunk_b(lane);
@@ -553,14 +552,8 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // buffer, row m (chunk 0, k = 0..7) or, for k = 8..15, the constant chunk chosen by bit 3 of m (chunk 2 or 3);
   // the B operand the constant chunk chosen by bit 4 of m (k = 0..7) or column m of the B part (chunk 1,
   // k = 8..15).  Region t adds 32 rows = AUG_REGION_STEP in either place.
-  uint32_t offA_aug, offB_aug;
-  {
-    const int m = lane & 31, upper = lane >> 5;
-    const int rowA = wm * 128 + m, rowB = wn * 64 + m;
-    const int chunkA = aug_chunk_a(lane), chunkB = aug_chunk_b(lane);
-    offA_aug = lds0 + (upper ? AUGC_OFF + 16 * (chunkA - 2) : AUG_OFF + rowA * 16);
-    offB_aug = lds0 + (upper ? AUG_OFF + AUG_PART_BYTES + rowB * 16 : AUGC_OFF + 16 * (chunkB - 2));
-  }
+  const uint32_t offA_aug = lds0 + AUG_OFF + aug_lds_offset_a(lane, wm * 128);
+  const uint32_t offB_aug = lds0 + AUG_OFF + aug_lds_offset_b(lane, wn * 64);
   typedef const __attribute__((address_space(3))) char* lds_cptr;
   typedef const __attribute__((address_space(3))) half8* lds_h8ptr;
   // fragment t (points 16 t .. 16 t + 15 of the wave tile's rows or columns); off: offA or offB (+ stage offset)

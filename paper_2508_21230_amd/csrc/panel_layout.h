@@ -82,13 +82,35 @@ EJ_LAYOUT_HD void mfma32_element(int lane, int q, int& m, int& n) {
 //   row m of the A operand = { P(x), P(x + 4), C [bit 3 of m = 0], C [bit 3 of m = 1] },  x = aug_row_point(m)
 //   row n of the B operand = { C [bit 4 of n = 0], C [bit 4 of n = 1], P(y), P(y + 16) },  y = aug_col_point(n)
 // (k = 0..15 left to right).  Of the 16 products of an element 6 are non-zero and each is exact, as in a plain
-// { P, C } . { C, P } step.  The operands are stored ready made in one more 64-byte row per point (point = row,
-// chunk c at position c ^ swz(row)): row m of a group of 32 holds
+// { P, C } . { C, P } step.  Written as four 16-byte chunks per row: row m of a group of 32 has
 //   chunk 0 = { P(x), P(x + 4) }   chunk 1 = { P(y), P(y + 16) }   chunk 2 = { C, 0 }   chunk 3 = { 0, C }
 // and lane l of the MFMA (row or column l % 32, k = 8 (l / 32) .. + 7) reads chunk aug_chunk_a(l) / aug_chunk_b(l).
 EJ_LAYOUT_HD int aug_row_point(int m) { return 16 * (m >> 4) + 8 * ((m >> 2) & 1) + (m & 3); }
 EJ_LAYOUT_HD int aug_col_point(int n) { return n & 15; }
 EJ_LAYOUT_HD int aug_chunk_a(int lane) { return (lane >> 5) ? 2 + ((lane >> 3) & 1) : 0; }
 EJ_LAYOUT_HD int aug_chunk_b(int lane) { return (lane >> 5) ? 1 : 2 + ((lane >> 4) & 1); }
+
+// Where the join kernel finds these chunks.  Chunks 2 and 3 are the same for every row, so only chunks 0 and 1 are
+// stored per row: a panel's augmentation block in the packed copy (its last k-block, 1024 units of 16 bytes) holds
+// chunk c (0 or 1) of row r (0..255) at unit aug_block_unit(r, c); its other 512 units are not used.
+EJ_LAYOUT_HD int aug_block_unit(int row, int chunk) { return chunk * 256 + row; }
+// A tile's augmentation buffer in the LDS: units 0..255 of the row panel's block (chunk 0 of its rows), units 256..511
+// of the column panel's block (chunk 1 of its rows), then the constant chunks: chunk 2 at EJ_AUG_CONST + 512 t,
+// chunk 3 sixteen bytes further, for t = 0..3 -- so that, for every lane of an operand read, region t of a wave tile
+// (32 rows further on) is 512 bytes further on.
+constexpr int EJ_AUG_PART = 256 * 16;
+constexpr int EJ_AUG_CONST = 2 * EJ_AUG_PART;
+constexpr int EJ_AUG_REGION_STEP = 32 * 16;
+constexpr int EJ_AUG_BYTES = EJ_AUG_CONST + 4 * EJ_AUG_REGION_STEP;
+// Byte offset in that buffer of the 16 bytes lane `lane` reads as its part of the A (B) operand of region t of the wave
+// tile whose first row (column) is row0 of the panel: aug_lds_offset_x(lane, row0) + t * EJ_AUG_REGION_STEP.
+EJ_LAYOUT_HD uint32_t aug_lds_offset_a(int lane, int row0) {
+  const int c = aug_chunk_a(lane);
+  return (uint32_t)(c == 0 ? 16 * (row0 + (lane & 31)) : EJ_AUG_CONST + 16 * (c - 2));
+}
+EJ_LAYOUT_HD uint32_t aug_lds_offset_b(int lane, int col0) {
+  const int c = aug_chunk_b(lane);
+  return (uint32_t)(c == 1 ? EJ_AUG_PART + 16 * (col0 + (lane & 31)) : EJ_AUG_CONST + 16 * (c - 2));
+}
 
 #endif  // EJOIN_PANEL_LAYOUT_H

@@ -30,4 +30,10 @@ int32_t ejoin_test_aug_row_point(int32_t m) { return aug_row_point(m); }
 int32_t ejoin_test_aug_col_point(int32_t n) { return aug_col_point(n); }
 int32_t ejoin_test_aug_chunk_a(int32_t lane) { return aug_chunk_a(lane); }
 int32_t ejoin_test_aug_chunk_b(int32_t lane) { return aug_chunk_b(lane); }
+int32_t ejoin_test_aug_block_unit(int32_t row, int32_t chunk) { return aug_block_unit(row, chunk); }
+uint32_t ejoin_test_aug_lds_offset_a(int32_t lane, int32_t row0) { return aug_lds_offset_a(lane, row0); }
+uint32_t ejoin_test_aug_lds_offset_b(int32_t lane, int32_t col0) { return aug_lds_offset_b(lane, col0); }
+int32_t ejoin_test_aug_const(int32_t which) {
+  return which == 0 ? EJ_AUG_PART : which == 1 ? EJ_AUG_CONST : which == 2 ? EJ_AUG_REGION_STEP : EJ_AUG_BYTES;
+}
 }

@@ -29,6 +29,9 @@ def lay(request, tmp_path_factory):
     lib.ejoin_test_place_of.restype = ctypes.c_int64
     lib.ejoin_test_fragment_offset.argtypes = [ctypes.c_int32, ctypes.c_int32]
     lib.ejoin_test_fragment_offset.restype = ctypes.c_uint32
+    for f in (lib.ejoin_test_aug_lds_offset_a, lib.ejoin_test_aug_lds_offset_b):
+        f.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        f.restype = ctypes.c_uint32
 
     def stored_at(row, p):
         point, chunk = ctypes.c_int64(), ctypes.c_int32()
@@ -111,3 +114,34 @@ def test_the_augmentation_step_adds_each_register_its_own_pairs_norm_terms(lay):
             assert D[m.value, n.value] == 7 * P[i.value].sum() + 7 * Q[j.value].sum()
             seen.add((i.value, j.value))
     assert len(seen) == 32 * 32  # every pair of the region in exactly one register
+
+
+def test_the_augmentation_buffer_hands_every_lane_the_chunk_its_operand_needs(lay):
+    """The join kernel copies units 0..255 of the row panel's augmentation block and units 256..511 of the column
+    panel's to the LDS and keeps the two constant chunks beside them; for every wave tile (rows 128 wm .., columns
+    64 wn ..), region t and lane, the 16 bytes at the operand's address must be the chunk the step's operand layout
+    asks for (chunk aug_chunk_a / aug_chunk_b of row / column 32 t + lane % 32 of the wave tile)."""
+    part, const, step, size = (lay.ejoin_test_aug_const(k) for k in range(4))
+    units = {}  # byte offset in the buffer -> what the 16 bytes there are
+    for r in range(256):
+        ua, ub = lay.ejoin_test_aug_block_unit(r, 0), lay.ejoin_test_aug_block_unit(r, 1)
+        assert 0 <= ua < 256 and 256 <= ub < 512  # the first 4 KB and the second 4 KB of the block: what is copied
+        units[16 * ua] = ("rowpanel", r, 0)                 # A part: the row panel's units 0..255 land at byte 0
+        units[part + 16 * (ub - 256)] = ("colpanel", r, 1)  # B part: the column panel's units 256..511 land at `part`
+    for t in range(4):
+        units[const + step * t] = ("const", 2)
+        units[const + step * t + 16] = ("const", 3)
+    assert len(units) == 512 + 8 and max(units) + 16 <= size
+    for wm in range(2):
+        for wn in range(4):
+            for lane in range(64):
+                ca, cb = lay.ejoin_test_aug_chunk_a(lane), lay.ejoin_test_aug_chunk_b(lane)
+                for t in range(4):
+                    got = units[lay.ejoin_test_aug_lds_offset_a(lane, 128 * wm) + step * t]
+                    assert got == (("rowpanel", 128 * wm + 32 * t + lane % 32, 0) if ca == 0 else ("const", ca))
+                for t in range(2):
+                    got = units[lay.ejoin_test_aug_lds_offset_b(lane, 64 * wn) + step * t]
+                    assert got == (("colpanel", 64 * wn + 32 * t + lane % 32, 1) if cb == 1 else ("const", cb))
+    # 32 consecutive lanes of a data read cover 512 contiguous bytes (no bank conflict); the other 32 read one constant
+    offs = [lay.ejoin_test_aug_lds_offset_a(lane, 128) for lane in range(32)]
+    assert offs == list(range(offs[0], offs[0] + 512, 16))
