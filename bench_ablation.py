@@ -12,9 +12,11 @@ Prints one JSON line per (variant, workload) and a markdown table.
     python bench_ablation.py --variant no_swizzle --workloads 3 --n 400000 --steps 1     (one variant: counter runs under rocprofv3)
     python bench_ablation.py --experiments [--workloads 3,4,5]
 
---experiments runs the two timing-only builds (results meaningless, see the top of csrc/ejoin.hip):
+--experiments runs the timing-only builds (results meaningless, see the top of csrc/ejoin.hip):
   hot_panels   every copy hits in the L2; join time and shader clock beside the full kernel's on the same data --
                what the memory-side fetch of the operand panels costs in clock on real operands;
+  no_copies    no global->LDS copies after the first four slices: MFMAs, LDS reads and barriers as they are,
+               on the operand bits those slices left in the LDS -- what feeding the LDS costs altogether;
   cycle_marks  s_memtime marks between the sections of a tile -- where a tile's time goes, per kind of wavefront.
 Each variant also passes the parity rule against the CPU oracle on small cases (tests/test_gpu_ablations.py).
 """
@@ -36,7 +38,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--n", type=int, default=None, help="override the number of points (quick runs)")
     ap.add_argument("--variant", default=None, help="run this variant only ('full', 'no_symmetry' or a name of build.ABLATIONS)")
-    ap.add_argument("--experiments", action="store_true", help="run the timing-only builds hot_panels and cycle_marks instead")
+    ap.add_argument("--experiments", action="store_true", help="run the timing-only builds hot_panels, no_copies and cycle_marks instead")
     args = ap.parse_args()
     if args.experiments:
         return experiments(args)
@@ -155,9 +157,12 @@ def experiments(args):
         npairs = torch.zeros(1, dtype=torch.int64, device="cuda:0")
         tiles = pkg.tiles_evaluated(n)
         flop = 2.0 * 65536 * ((d + 63) // 64 * 64) * tiles
-        for name in ("full", "hot_panels", "full", "hot_panels"):
-            ej = pkg.EJoin(0, lib_path=None if name == "full" else os.path.join(build.ABLATION_DIR, f"libejoin_{name}.so"))
-            step = lambda: ej.selfjoin_pairs(Xd, eps, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
+        # (no_copies computes every tile on the first tile's operands: compared output-free, epsilon = 0, so that the
+        # rare path sees no more than the duplicates in either build)
+        for name in ("full", "hot_panels", "full eps=0", "no_copies", "full", "hot_panels", "full eps=0", "no_copies"):
+            ej = pkg.EJoin(0, lib_path=None if name.startswith("full") else os.path.join(build.ABLATION_DIR, f"libejoin_{name}.so"))
+            eps_run = 0.0 if name in ("full eps=0", "no_copies") else eps
+            step = lambda: ej.selfjoin_pairs(Xd, eps_run, cap, pairs=pairs, dist2=d2, n_pairs=npairs)
             step()
             torch.cuda.synchronize()
             ej.set_profiling(True)

@@ -30,6 +30,7 @@ ABLATIONS = {
 #: measurement builds whose results are meaningless (timing only; see the top of csrc/ejoin.hip and bench_ablation.py --experiments)
 EXPERIMENTS = {
     "hot_panels": ["-DEJOIN_EXP_HOT_PANELS"],
+    "no_copies": ["-DEJOIN_EXP_NO_COPIES"],
     "cycle_marks": ["-DEJOIN_EXP_CYCLE_MARKS"],
 }
 ABLATION_DIR = os.path.join(PKG, "ablation")

@@ -40,9 +40,13 @@ constexpr int KSLICE = 32;    // coordinates per LDS stage (64 B per row)
 #ifndef EJOIN_ABL_NSTAGE
 #define EJOIN_ABL_NSTAGE 4
 #endif
-// Two measurement builds whose RESULTS ARE MEANINGLESS (timing only, never loaded by the product path or the tests):
+// Three measurement builds whose RESULTS ARE MEANINGLESS (timing only, never loaded by the product path or the tests):
 // EJOIN_EXP_HOT_PANELS: every global->LDS copy reads one of four panels, so that every copy hits in the L2 while
 //   tiles, MFMAs, LDS traffic and operand values stay what they are -- what the memory-side fetch costs in clock.
+// EJOIN_EXP_NO_COPIES: after the first NSTAGE slices and the first tile's augmentation operands no global->LDS copy is
+//   issued at all, and the rare path is switched off: every later slice computes on what those copies left in the LDS --
+//   the same MFMAs, LDS reads and barriers on real operand bits with the copy path, the L2 and the fabric idle: what
+//   feeding the LDS costs in cycles and clock (compared with the full kernel at epsilon = 0).
 // EJOIN_EXP_CYCLE_MARKS: s_memtime marks between the sections of a tile; the per-section sums of all wavefronts
 //   are added into the last 16 u64 of the pair buffer (waves 0-3, then waves 4-7) -- where a tile's cycles go.
 #ifdef EJOIN_EXP_HOT_PANELS
@@ -468,7 +472,9 @@ __device__ __forceinline__ void xcd_align(uint32_t* bar, uint32_t expect) {
   __syncthreads();
 }
 
-template <bool COUNT>
+// KEEP_A: the instance for tiles of exactly NSTAGE slices (96 < d <= 128), which leaves a row panel in the LDS across
+// the consecutive tiles that share it (see keep_a_cur); the other instance carries none of that logic.
+template <bool COUNT, bool KEEP_A>
 __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   // the largest norm of the call has been consumed by k_aux: cleared here for the next call
@@ -508,13 +514,15 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
     return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
   };
-  auto issue_slice = [&](const char* pa_, const char* pb_, uint32_t lds_stage /* LDS address of the stage + cw*1024 */) {
+  auto issue_slice = [&](const char* pa_, const char* pb_, uint32_t lds_stage /* LDS address of the stage + cw*1024 */, bool keep_a) {
     const char* pa = uniform_ptr(pa_);
     const char* pb = uniform_ptr(pb_);
-    copy16_to_lds<0>(lds_stage, pa, voff0);
-    copy16_to_lds<4096>(lds_stage, pa, voff0 + 4096);
-    copy16_to_lds<8192>(lds_stage, pa, voff0 + 8192);
-    copy16_to_lds<12288>(lds_stage, pa, voff0 + 12288);
+    if (!(KEEP_A && keep_a)) {
+      copy16_to_lds<0>(lds_stage, pa, voff0);
+      copy16_to_lds<4096>(lds_stage, pa, voff0 + 4096);
+      copy16_to_lds<8192>(lds_stage, pa, voff0 + 8192);
+      copy16_to_lds<12288>(lds_stage, pa, voff0 + 12288);
+    }
     copy16_to_lds<PANEL_BYTES>(lds_stage, pb, voff0);
     copy16_to_lds<PANEL_BYTES + 4096>(lds_stage, pb, voff0 + 4096);
     copy16_to_lds<PANEL_BYTES + 8192>(lds_stage, pb, voff0 + 8192);
@@ -525,7 +533,14 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   // copy instruction each per copying wave, into a buffer of their own.  Issued in the tile's first slice (every
   // wave has then left the tile before and its reads of the buffer behind), read in its last.
   constexpr int NAUG = 2;
+#ifdef EJOIN_EXP_NO_COPIES
+  bool aug_copied = false;
+#endif
   auto issue_aug = [&](uint32_t I, uint32_t J) {
+#ifdef EJOIN_EXP_NO_COPIES
+    if (aug_copied) return;
+    aug_copied = true;
+#endif
     const char* ga = uniform_ptr(XbA + (int64_t)EJ_PANEL_A(I) * panel_stride + (int64_t)nsl * PANEL_BYTES);
     const char* gb = uniform_ptr(XbB + (int64_t)EJ_PANEL_B(J) * panel_stride + (int64_t)nsl * PANEL_BYTES);
     copy16_to_lds<AUG_OFF>(lds0 + cw * 1024, ga, voff0);
@@ -645,13 +660,23 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
   int iks = 0;
   int ahead = 0;
   bool issue_live = true;       // the issue cursor points at real work
+  // KEEP_A (a tile has exactly as many slices as the ring has stages, 96 < d <= 128): slice ks of every tile lands in
+  // stage ks.  Three of four consecutive tiles of a workgroup have the same row panel (tile_cursor.h): the A half of
+  // each stage then already holds what the next tile needs, and the copies of its A panel are left out (NCOPY / 2 per
+  // slice instead of NCOPY; the counted waits are told through the flags of the tile being issued, the tile being
+  // computed and the one after it).
+  uint32_t issue_I = I;
+  bool keep_a_issue = false, keep_a_cur = false, keep_a_next = false;
   const char* pa = XbA + (int64_t)EJ_PANEL_A(I) * panel_stride;
   const char* pb = XbB + (int64_t)EJ_PANEL_B(J) * panel_stride;
   const uint32_t lds_w = lds0 + cw * 1024;
   auto issue_one = [&](uint32_t Gissue) {
     if (!copier) return;
+#ifdef EJOIN_EXP_NO_COPIES
+    if (Gissue >= (uint32_t)NSTAGE) return;
+#endif
     if (issue_live) {
-      issue_slice(pa, pb, lds_w + (Gissue % NSTAGE) * STAGE_BYTES);
+      issue_slice(pa, pb, lds_w + (Gissue % NSTAGE) * STAGE_BYTES, keep_a_issue);
     } else {
 #pragma unroll
       for (int q = 0; q < NCOPY; ++q) copy16_to_lds<0>(lds0 + DUMP_OFF, XbA, lane * 16);
@@ -666,6 +691,11 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
       const uint32_t ti = first_after ? In : In2, tj = first_after ? Jn : Jn2;
       pa = XbA + (int64_t)(issue_live ? EJ_PANEL_A(ti) : 0) * panel_stride;
       pb = XbB + (int64_t)(issue_live ? EJ_PANEL_B(tj) : 0) * panel_stride;
+      if constexpr (KEEP_A) {
+        keep_a_issue = issue_live && ti == issue_I;
+        keep_a_next = keep_a_issue;  // (with nsl == NSTAGE the cursor is one tile ahead at every wrap)
+        issue_I = ti;
+      }
     }
   };
   for (int q = 0; q < DIST; ++q) issue_one(q);
@@ -765,7 +795,12 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     //     tile's second slice, the augmentation copies issued in its first between those of slices G+1 and G+2
     //     (from the third slice on they are older than everything that may be outstanding: they have landed, and
     //     the barrier of that slice makes them visible, before the last slice reads them)
-    if (COPIER && DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
+    //     A tile whose A panel was kept has NCOPY / 2 copies per slice; the slice two ahead belongs to the tile being
+    //     computed in its first two slices and to the next one after that (KEEP_A: nsl == NSTAGE).
+    if (KEEP_A && COPIER && ((FIRST || second) ? keep_a_cur : keep_a_next)) {
+      if (DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY / 2 * (DIST - 2) + NAUG) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY / 2 * (DIST - 2)) : "memory");
+    } else if (COPIER && DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
     else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
@@ -872,6 +907,9 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
 #ifdef EJOIN_ABL_NOPREFILTER
       blocks_hit = 0xFF;
 #endif
+#ifdef EJOIN_EXP_NO_COPIES
+      blocks_hit = 0;  // (every tile holds the first tile's distances: keep the rare path out of the comparison)
+#endif
       if (skip) blocks_hit = 0;
       else if (diag && !COUNT) blocks_hit |= diag_blocks;  // self pairs are emitted whatever the arithmetic says
       // rare path, one block at a time.  Two instances: the common one for tiles off the diagonal, and
@@ -972,6 +1010,7 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     Jn = Jn2;
     have_next = have_next2;
     --ahead;  // (at least 1 before: the issue cursor has left the tile that was just finished)
+    if constexpr (KEEP_A) keep_a_cur = keep_a_next;
     if (have) {
       if (--sync_left == 0) {
         sync_left = (uint32_t)a.sync_mode;
@@ -1256,7 +1295,8 @@ int launch_join(ejoin_ctx* ctx, const Workspace& w, bool own, const Operand& A, 
     EJ_TRY(hipEventRecord(ctx->ev[1], st));
     EJ_TRY(hipEventRecord(ctx->ev[2], st));
   }
-  hipLaunchKernelGGL(k_join<COUNT>, dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
+  if (a.nslices == NSTAGE) hipLaunchKernelGGL((k_join<COUNT, true>), dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
+  else hipLaunchKernelGGL((k_join<COUNT, false>), dim3(ctx->num_cu), dim3(THREADS), LDS_BYTES, st, a);
   EJ_TRY(hipGetLastError());
   if (own) ctx->ws_dirty = false;
   if (ctx->profiling) {
@@ -1424,8 +1464,10 @@ int ejoin_create(ejoin_ctx** out, int device) {
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking);
   for (int i = 0; i < EJOIN_MAX_BATCHES && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ctx->batch_ev[i], hipEventDisableTiming);
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->batch_count), EJOIN_MAX_BATCHES * sizeof(unsigned long long), hipHostMallocDefault);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false, false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true, false>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_join<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     ejoin_destroy(ctx);

@@ -147,11 +147,14 @@ def test_edge_sizes(ej, n, d):
     parity.check_pair_sets(P, eps, pairs, d2, ora_pairs, ora_d2)
 
 
-@pytest.mark.parametrize("n,d", [(6500, 64), (7000, 40), (6200, 128), (5900, 192), (12000, 64), (11000, 24)])
+@pytest.mark.parametrize("n,d", [(6500, 64), (7000, 40), (6200, 128), (5900, 192), (12000, 64), (11000, 24), (12000, 128), (11000, 100)])
 def test_more_tiles_than_workgroups_at_small_d(ej, n, d):
     """Every workgroup walks several tiles (351 .. 406 tiles on 256 workgroups; 946 and 1128 in the last two cases,
     four to five per workgroup).  At d <= 64 a tile has two slices and the copy pipeline runs three ahead: the copy
-    cursor works on the tile after the next one while the current one is still being computed."""
+    cursor works on the tile after the next one while the current one is still being computed.  At 96 < d <= 128 a tile
+    has as many slices as the LDS ring has stages, and a row panel stays in the LDS across the consecutive tiles of a
+    workgroup that share it (the last two cases: four to five tiles per workgroup, three of four with the row of the
+    tile before)."""
     print(f"multi-tile n={n} d={d}", flush=True)
     rng = np.random.default_rng(n + d)
     X = rng.random((n, d), dtype=np.float32).astype(np.float16).view(np.uint16)

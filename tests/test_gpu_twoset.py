@@ -76,7 +76,7 @@ def test_two_set_pairs_against_oracle(ej, w, n_p, n_q, S):
     assert none is None and int(total2.cpu()[0]) == found and torch.equal(cp2, cp)
 
 
-@pytest.mark.parametrize("d,n_p,n_q", [(64, 4200, 4400), (128, 4200, 4400), (64, 9000, 7100)])
+@pytest.mark.parametrize("d,n_p,n_q", [(64, 4200, 4400), (128, 4200, 4400), (64, 9000, 7100), (128, 8000, 9100)])
 def test_two_set_more_tiles_than_workgroups(ej, d, n_p, n_q):
     # 17 x 18 = 306 tiles on 256 workgroups, or 36 x 28 = 1008 (about four per workgroup); at d <= 64 a tile has fewer
     # slices than the copies run ahead, and the copy cursor is two tiles ahead of the tile being computed
