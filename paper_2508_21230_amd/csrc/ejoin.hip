@@ -529,9 +529,16 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     copy16_to_lds<PANEL_BYTES + 12288>(lds_stage, pb, voff0 + 12288);
   };
   constexpr int NCOPY = 8;  // copy instructions per slice and copying wave
-  // The operands of a tile's augmentation step: 4 KB of panel I's augmentation block and 4 KB of panel J's, one
-  // copy instruction each per copying wave, into a buffer of their own.  Issued in the tile's first slice (every
-  // wave has then left the tile before and its reads of the buffer behind), read in its last.
+  // The operands of a tile's augmentation step: 4 KB of panel I's augmentation block and 4 KB of panel J's, into a
+  // buffer of their own: eight copy instructions per tile, issued in the tile's first slice (every wave has then left the
+  // tile before and its reads of the buffer behind) and read in its last.  In the general instance they are the job of
+  // the four waves that do not copy slices, two each, behind their MFMAs of the first slice: they have nothing to do from
+  // there to the next barrier, and their copies do not enter the counted waits of the copying waves; they wait for them
+  // (nothing else of theirs is outstanding) before the barrier of the tile's last slice.  In the KEEP_A instance, where
+  // the copying waves have half the copies and the others no time to spare, the copying waves issue them ahead of the
+  // slice's copies (NAUG each) and allow for them in the one counted wait where they are younger than what must have
+  // landed (a tile's second slice; from the third on they are older than everything that may be outstanding).
+  constexpr bool AUG_BY_IDLE_WAVES = !KEEP_A;
   constexpr int NAUG = 2;
 #ifdef EJOIN_EXP_NO_COPIES
   bool aug_copied = false;
@@ -791,25 +798,33 @@ __global__ __launch_bounds__(THREADS) void k_join(const JoinArgs a) {
     constexpr bool FIRST = decltype(first_c)::value;
     constexpr bool COPIER = decltype(copier_c)::value;
     const uint32_t st_cur = (G % NSTAGE) * STAGE_BYTES, st_nxt = ((G + 1) % NSTAGE) * STAGE_BYTES;
-    // (a) this wave's copies of slice G+1 have landed once only those of slice G+2 are outstanding -- and, in a
-    //     tile's second slice, the augmentation copies issued in its first between those of slices G+1 and G+2
-    //     (from the third slice on they are older than everything that may be outstanding: they have landed, and
-    //     the barrier of that slice makes them visible, before the last slice reads them)
+    // (a) this wave's copies of slice G+1 have landed once only those of slice G+2 are outstanding.
     //     A tile whose A panel was kept has NCOPY / 2 copies per slice; the slice two ahead belongs to the tile being
     //     computed in its first two slices and to the next one after that (KEEP_A: nsl == NSTAGE).
-    if (KEEP_A && COPIER && ((FIRST || second) ? keep_a_cur : keep_a_next)) {
+    //     The waves that do not copy slices have at most the tile's augmentation copies outstanding, which must have
+    //     landed before the barrier of the last slice.
+    constexpr bool LAST_ = decltype(last_c)::value;
+    if constexpr (!COPIER) {
+      if constexpr (AUG_BY_IDLE_WAVES && LAST_) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else if constexpr (AUG_BY_IDLE_WAVES) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
+    } else if (KEEP_A && ((FIRST || second) ? keep_a_cur : keep_a_next)) {
       if (DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY / 2 * (DIST - 2) + NAUG) : "memory");
       else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY / 2 * (DIST - 2)) : "memory");
-    } else if (COPIER && DIST >= 3 && second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
-    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
+    } else if (DIST >= 3 && second) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2) + NAUG) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCOPY * (DIST - 2)) : "memory");
+    }
     // (b) after the barrier slice G+1 is complete in LDS for everybody, and everybody is done with slice G-1
     wg_barrier();
     // (c) the copying waves refill the stage slice G-1 occupied with slice G+DIST, while the other wave of
     //     their SIMD starts on the MFMAs of the slice
-    if constexpr (COPIER && FIRST) issue_aug(I, J);
+    if constexpr (COPIER && FIRST && !AUG_BY_IDLE_WAVES) issue_aug(I, J);
     if constexpr (COPIER) issue_one(G + DIST);
     // (d) the MFMAs of slice G, overlapped with the LDS reads of what follows
     mma_slice(first_c, last_c, st_cur, st_nxt);
+    if constexpr (!COPIER && FIRST && AUG_BY_IDLE_WAVES) issue_aug(I, J);
     ++G;
   };
 
