@@ -37,7 +37,7 @@ PEAK_CLOCK_MHZ = 2400.0
 HEADLINE = (4, 16, "pairs")
 # every configuration and mode the benchmark spec names: (workload id = configs index + 1, selectivity, mode)
 ALL_CASES = [(1, 32, "pairs"), (2, 64, "pairs"), (3, 16, "pairs"), (4, 16, "pairs"), (4, 128, "pairs"), (4, 1024, "pairs"),
-             (5, 64, "pairs"), (5, 64, "count")]
+             (4, 1024, "count"), (5, 64, "pairs"), (5, 64, "count")]
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "k_join_workload4_hbm_counters.txt")
 KERNEL_SOURCES = [os.path.join(ROOT, "paper_2508_21230_amd", "csrc", f) for f in ("ejoin.hip", "panel_layout.h", "tile_cursor.h")]
 
