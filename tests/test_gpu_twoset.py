@@ -91,6 +91,12 @@ def test_two_set_more_tiles_than_workgroups(ej, d, n_p, n_q):
     gp, gd2, found = parity.to_host_pairs(pairs, d2, npairs)
     assert found == gp.shape[0]
     print("  ", check_two_set(P, Q, eps, gp, gd2, op, od2), flush=True)
+    # count mode walks the same schedule
+    cp, cq, total = ej.join_count(dev(XP), dev(XQ), float(eps))
+    torch.cuda.synchronize()
+    assert int(total.cpu()[0]) == found
+    assert np.array_equal(cp.cpu().numpy().view(np.uint32), np.bincount(gp[:, 0], minlength=n_p))
+    assert np.array_equal(cq.cpu().numpy().view(np.uint32), np.bincount(gp[:, 1], minlength=n_q))
 
 
 def test_two_set_join_of_a_set_with_itself_matches_the_self_join(ej):
